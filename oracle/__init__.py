@@ -1,0 +1,172 @@
+"""CPU oracle for pack -> ragged attention -> unpack (test infrastructure, NOT the product).
+
+Thin ctypes wrapper over ``ragged_oracle.c`` (plain C, fp64 arithmetic).  Only ``tests/``,
+``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import this package.
+It imports nothing from the HIP package and the HIP package imports nothing from here.
+
+All arrays are NumPy.  16-bit floating inputs travel as raw ``uint16`` words plus a dtype tag
+("f16" or "bf16"), because NumPy has no bfloat16; the C code decodes them to double itself.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "ragged_oracle.c"
+_LIB = _HERE / "libragged_oracle.so"
+_DTYPES = {"f16": 0, "bf16": 1}
+
+_lib = None
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math).  Rebuilds when the source is newer."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        subprocess.run(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+             "-o", str(tmp), str(_SRC), "-lm"],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        lib.oracle_decode.argtypes = [vp, i64, i32, vp]
+        lib.oracle_decode.restype = None
+        lib.oracle_pack.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+        lib.oracle_pack.restype = i64
+        lib.oracle_unpack.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32]
+        lib.oracle_unpack.restype = None
+        lib.oracle_attn.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, ctypes.c_float, vp, i32]
+        lib.oracle_attn.restype = i32
+        lib.oracle_attn_row.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, i32,
+                                        ctypes.c_float, vp, vp]
+        lib.oracle_attn_row.restype = i32
+        lib.oracle_max_threads.argtypes = []
+        lib.oracle_max_threads.restype = i32
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _words(a, shape_len=None) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype == np.int16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16:
+        raise TypeError(f"expected raw 16-bit words (uint16/int16/float16), got {a.dtype}")
+    if shape_len is not None and a.ndim != shape_len:
+        raise ValueError(f"expected {shape_len} dimensions, got shape {a.shape}")
+    return a
+
+
+def _mask(keep, B=None, N=None) -> np.ndarray:
+    keep = np.ascontiguousarray(keep)
+    if keep.dtype == np.bool_:
+        keep = keep.view(np.uint8)
+    if keep.dtype != np.uint8 or keep.ndim != 2:
+        raise TypeError("keep must be a [B, N] uint8/bool array")
+    if B is not None and keep.shape != (B, N):
+        raise ValueError(f"keep shape {keep.shape} != {(B, N)}")
+    return keep
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def decode(words, dtype: str) -> np.ndarray:
+    """Raw 16-bit words -> float64, exactly."""
+    w = _words(words)
+    out = np.empty(w.shape, dtype=np.float64)
+    _load().oracle_decode(_ptr(w), w.size, _DTYPES[dtype], _ptr(out))
+    return out
+
+
+def pack(x_words, keep):
+    """x_words [B,N,C] words, keep [B,N] -> (packed [T,C] words, cu_seqlens [B+1] i32, gather_idx [T] i32)."""
+    x = _words(x_words, 3)
+    B, N, C = x.shape
+    keep = _mask(keep, B, N)
+    packed = np.zeros((B * N, C), dtype=np.uint16)
+    cu = np.zeros(B + 1, dtype=np.int32)
+    gidx = np.zeros(B * N, dtype=np.int32)
+    T = int(_load().oracle_pack(_ptr(x), _ptr(keep), B, N, C, _ptr(packed), _ptr(cu), _ptr(gidx)))
+    return packed[:T].copy(), cu, gidx[:T].copy()
+
+
+def unpack(src_words, keep, cu_seqlens, C: int, fill_mode: int, out_init=None) -> np.ndarray:
+    """src [T,C] words -> out [B,N,C] words.  fill_mode 0 keeps ``out_init`` on dropped rows."""
+    src = _words(src_words, 2)
+    keep = _mask(keep)
+    B, N = keep.shape
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    if cu.shape != (B + 1,):
+        raise ValueError("cu_seqlens must have B+1 entries")
+    if src.shape != (int(cu[B]), C):
+        raise ValueError(f"src shape {src.shape} != {(int(cu[B]), C)}")
+    if fill_mode not in (0, 1):
+        raise ValueError("fill_mode must be 0 or 1")
+    if out_init is None:
+        out = np.zeros((B, N, C), dtype=np.uint16)
+    else:
+        out = _words(out_init, 3).copy()
+        if out.shape != (B, N, C):
+            raise ValueError("out_init shape mismatch")
+    _load().oracle_unpack(_ptr(src), _ptr(keep), _ptr(cu), B, N, C, _ptr(out), fill_mode)
+    return out
+
+
+def _check_qkv(q, k, v, cu):
+    q, k, v = _words(q, 3), _words(k, 3), _words(v, 3)
+    if not (q.shape == k.shape == v.shape):
+        raise ValueError("q, k, v shapes differ")
+    cu = np.ascontiguousarray(cu, dtype=np.int32)
+    if cu.ndim != 1 or cu.size < 1 or cu[0] != 0 or np.any(np.diff(cu) < 0):
+        raise ValueError("cu_seqlens must start at 0 and be non-decreasing")
+    if int(cu[-1]) != q.shape[0]:
+        raise ValueError(f"cu_seqlens[-1]={int(cu[-1])} but q has {q.shape[0]} rows")
+    return q, k, v, cu
+
+
+def attn(q, k, v, cu_seqlens, scale: float, dtype: str = "f16", threads: int = 1) -> np.ndarray:
+    """softmax(scale * q k^T) v per image and head, fp64.  q,k,v [T,H,D] words -> [T,H,D] float64."""
+    q, k, v, cu = _check_qkv(q, k, v, cu_seqlens)
+    T, H, D = q.shape
+    out = np.zeros((T, H, D), dtype=np.float64)
+    rc = _load().oracle_attn(_ptr(q), _ptr(k), _ptr(v), _DTYPES[dtype], _ptr(cu), cu.size - 1,
+                             H, D, float(scale), _ptr(out), int(threads))
+    if rc != 0:
+        raise MemoryError("oracle_attn failed to allocate scratch")
+    return out
+
+
+def attn_row(q, k, v, cu_seqlens, i: int, h: int, r: int, scale: float, dtype: str = "f16"):
+    """(probabilities p_j/L over image i's keys, output row) for query r of image i, head h."""
+    q, k, v, cu = _check_qkv(q, k, v, cu_seqlens)
+    T, H, D = q.shape
+    n = int(cu[i + 1] - cu[i])
+    probs = np.zeros(n, dtype=np.float64)
+    o = np.zeros(D, dtype=np.float64)
+    rc = _load().oracle_attn_row(_ptr(q), _ptr(k), _ptr(v), _DTYPES[dtype], _ptr(cu), i, h, r,
+                                 H, D, float(scale), _ptr(probs), _ptr(o))
+    if rc != 0:
+        raise IndexError("row out of range")
+    return probs, o

@@ -1,0 +1,244 @@
+/*
+ * ragged_oracle.c -- CPU reference ("oracle") for the pack -> ragged attention -> unpack path
+ * of "Dispatch-Aware Ragged Attention for Pruned Vision Transformers".
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the test-suite, the smoke check and the
+ * benchmark's cpu_baseline leg may call it.  It shares no code, header, table or helper with the
+ * HIP library; nothing in the GPU path may include or link this file.
+ *
+ * It is deliberately plain and slow: attention is the textbook definition evaluated in fp64, one
+ * query row at a time, with no tiling, no running maximum and no fusion.  The paper's Algorithm 1
+ * (online softmax over 64x64 tiles) reaches the same result up to rounding order, so the oracle is
+ * the definition itself (Section 4.2, "Ragged Attention Kernel": bidirectional attention, softmax
+ * of q.k/sqrt(d) over the tokens of the SAME image only, no causal mask, no dropout).
+ *
+ * Pack / unpack are exact integer / bit-copy operations (Section 4.1, "Fused Token Packing").
+ *
+ * Readings of the paper taken here (the paper is silent or loose on these points):
+ *   - softmax scale is an argument (Alg. 1 hard-codes 1/sqrt(d)); it is an fp32 value widened
+ *     to double before multiplying the fp64 dot product;
+ *   - only keys j < n_i of the same image take part (Alg. 1 loads whole tiles with no bound);
+ *   - packed order is stable: images ascending, tokens ascending inside an image
+ *     (Section 4.1 item 1: cumulative sums give the destination indices; Section 4.3 item 5
+ *     reads CLS from the front of each packed sequence);
+ *   - cu_seqlens and gather_idx are int32; the keep mask is one byte per token, nonzero = keep;
+ *   - a sequence with n_i = 0 contributes nothing and produces no output rows;
+ *   - unpack (named but not described by the paper) is the inverse scatter of pack; dropped rows
+ *     are either left untouched (fill_mode 0) or written with +0 words (fill_mode 1).
+ *
+ * Parity pins (tests/test_oracle_*.py): brute-force padded+masked attention written separately in
+ * NumPy; torch's float64 scaled_dot_product_attention for one sequence; closed forms (n=1,
+ * scale=0 -> mean of V, identical V rows, two-token sigmoid case, large-scale argmax limit);
+ * invariants (rows of softmax sum to 1, key-shift invariance, permutation equivariance, ragged
+ * isolation, convex hull); NumPy boolean indexing / cumsum / flatnonzero for pack and unpack.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F16 = 0, ORACLE_BF16 = 1 };
+
+/* IEEE binary16 -> double, exact (handles subnormals, infinities, NaN). */
+static double decode_f16(uint16_t w)
+{
+    int sign = (w >> 15) & 1;
+    int expo = (w >> 10) & 0x1f;
+    int frac = w & 0x3ff;
+    double mag;
+    if (expo == 0) {
+        mag = ldexp((double)frac, -24);              /* subnormal: frac * 2^-10 * 2^-14 */
+    } else if (expo == 31) {
+        mag = frac ? NAN : INFINITY;
+    } else {
+        mag = ldexp(1.0 + (double)frac / 1024.0, expo - 15);
+    }
+    return sign ? -mag : mag;
+}
+
+/* bfloat16 -> double, exact: a bfloat16 is the upper 16 bits of an IEEE binary32. */
+static double decode_bf16(uint16_t w)
+{
+    uint32_t bits = (uint32_t)w << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static double decode(uint16_t w, int dtype)
+{
+    return dtype == ORACLE_BF16 ? decode_bf16(w) : decode_f16(w);
+}
+
+/* Exposed so the tests can pin the decoders against NumPy / torch conversions. */
+void oracle_decode(const uint16_t *words, int64_t count, int dtype, double *out)
+{
+    for (int64_t e = 0; e < count; ++e) out[e] = decode(words[e], dtype);
+}
+
+/*
+ * Pack (Section 4.1).  x is [B, N, C] 16-bit words, keep is [B, N] bytes.
+ * Walks images then tokens in ascending order; every kept token appends its flat source row
+ * i*N+t to gather_idx and its C words to the next row of packed.
+ * cu_seqlens[0] = 0, cu_seqlens[i+1] = cu_seqlens[i] + n_i.
+ * Returns the total kept count T.  packed / gather_idx must have room for B*N rows / entries.
+ */
+int64_t oracle_pack(const uint16_t *x, const uint8_t *keep, int B, int N, int C,
+                    uint16_t *packed, int32_t *cu_seqlens, int32_t *gather_idx)
+{
+    int64_t next = 0;
+    cu_seqlens[0] = 0;
+    for (int i = 0; i < B; ++i) {
+        for (int t = 0; t < N; ++t) {
+            if (keep[(int64_t)i * N + t] != 0) {
+                int64_t src = (int64_t)i * N + t;
+                gather_idx[next] = (int32_t)src;
+                memcpy(packed + next * C, x + src * C, (size_t)C * sizeof(uint16_t));
+                ++next;
+            }
+        }
+        cu_seqlens[i + 1] = (int32_t)next;
+    }
+    return next;
+}
+
+/*
+ * Unpack: the inverse scatter of pack.  src is [T, C] words; out is [B, N, C] words.
+ * A kept token (i,t) with rank r among image i's kept tokens receives row cu_seqlens[i] + r of
+ * src.  Dropped tokens: fill_mode 1 writes +0 words, fill_mode 0 leaves out untouched.
+ * Walks the mask itself, so it does not depend on gather_idx being right.
+ */
+void oracle_unpack(const uint16_t *src, const uint8_t *keep, const int32_t *cu_seqlens,
+                   int B, int N, int C, uint16_t *out, int fill_mode)
+{
+    for (int i = 0; i < B; ++i) {
+        int64_t rank = 0;
+        for (int t = 0; t < N; ++t) {
+            uint16_t *dst = out + ((int64_t)i * N + t) * C;
+            if (keep[(int64_t)i * N + t] != 0) {
+                int64_t row = (int64_t)cu_seqlens[i] + rank;
+                memcpy(dst, src + row * C, (size_t)C * sizeof(uint16_t));
+                ++rank;
+            } else if (fill_mode == 1) {
+                memset(dst, 0, (size_t)C * sizeof(uint16_t));
+            }
+        }
+    }
+}
+
+/*
+ * One query row of one (image, head): the plain definition.
+ *   S_j = scale * sum_d q[d] k_j[d]          j in [0, n)
+ *   M   = max_j S_j ; p_j = exp(S_j - M) ; L = sum_j p_j
+ *   o[d] = (sum_j p_j v_j[d]) / L
+ * Subtracting M is the usual overflow guard; it cancels in p_j / L.
+ * probs (optional, length n) receives p_j / L.
+ */
+static void attend_row(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
+                       int64_t s, int n, int r, int h, int H, int D, double scale,
+                       double *scores, double *o, double *probs)
+{
+    const int64_t tok = (int64_t)H * D;            /* words between consecutive tokens */
+    const uint16_t *qrow = q + (s + r) * tok + (int64_t)h * D;
+    double M = -INFINITY;
+    for (int j = 0; j < n; ++j) {
+        const uint16_t *krow = k + (s + j) * tok + (int64_t)h * D;
+        double dot = 0.0;
+        for (int d = 0; d < D; ++d) dot += decode(qrow[d], dtype) * decode(krow[d], dtype);
+        scores[j] = scale * dot;
+        if (scores[j] > M) M = scores[j];
+    }
+    double L = 0.0;
+    for (int j = 0; j < n; ++j) {
+        scores[j] = exp(scores[j] - M);
+        L += scores[j];
+    }
+    for (int d = 0; d < D; ++d) o[d] = 0.0;
+    for (int j = 0; j < n; ++j) {
+        const uint16_t *vrow = v + (s + j) * tok + (int64_t)h * D;
+        for (int d = 0; d < D; ++d) o[d] += scores[j] * decode(vrow[d], dtype);
+    }
+    for (int d = 0; d < D; ++d) o[d] /= L;
+    if (probs) for (int j = 0; j < n; ++j) probs[j] = scores[j] / L;
+}
+
+/*
+ * Ragged attention (Section 4.2): q, k, v are [T, H, D] 16-bit words (token-major, then head,
+ * then head-dim), out is [T, H, D] doubles.  Image i owns rows [cu[i], cu[i+1]).
+ * threads <= 1 runs serially; otherwise (image, head) pairs are spread over that many OpenMP
+ * threads -- the arithmetic of every row is unchanged.  Returns 0, or -1 if scratch allocation
+ * failed.
+ */
+int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
+                const int32_t *cu_seqlens, int B, int H, int D, float scale,
+                double *out, int threads)
+{
+    int nmax = 0;
+    for (int i = 0; i < B; ++i) {
+        int n = cu_seqlens[i + 1] - cu_seqlens[i];
+        if (n > nmax) nmax = n;
+    }
+    if (nmax == 0) return 0;
+    if (threads < 1) threads = 1;
+    int failed = 0;
+    const int pairs = B * H;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads)
+#endif
+    {
+        double *scores = (double *)malloc((size_t)nmax * sizeof(double));
+        if (!scores) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int p = 0; p < pairs; ++p) {
+            if (!scores) continue;
+            int i = p / H, h = p % H;
+            int64_t s = cu_seqlens[i];
+            int n = cu_seqlens[i + 1] - cu_seqlens[i];
+            for (int r = 0; r < n; ++r) {
+                double *o = out + ((s + r) * (int64_t)H + h) * D;
+                attend_row(q, k, v, dtype, s, n, r, h, H, D, (double)scale, scores, o, NULL);
+            }
+        }
+        free(scores);
+    }
+    return failed ? -1 : 0;
+}
+
+/*
+ * Debug view for the "softmax rows sum to one" invariant: the normalised probabilities p_j / L
+ * of query row r of image i, head h (length n_i), plus that row's output.
+ */
+int oracle_attn_row(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
+                    const int32_t *cu_seqlens, int i, int h, int r, int H, int D, float scale,
+                    double *probs, double *o)
+{
+    int64_t s = cu_seqlens[i];
+    int n = cu_seqlens[i + 1] - cu_seqlens[i];
+    if (r < 0 || r >= n) return -1;
+    double *scores = (double *)malloc((size_t)n * sizeof(double));
+    if (!scores) return -1;
+    attend_row(q, k, v, dtype, s, n, r, h, H, D, (double)scale, scores, o, probs);
+    free(scores);
+    return 0;
+}
+
+/* Number of OpenMP threads a parallel region would get by default (1 without OpenMP). */
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
