@@ -131,24 +131,24 @@ void oracle_unpack(const uint16_t *src, const uint8_t *keep, const int32_t *cu_s
 }
 
 /*
- * One query row of one (image, head): the plain definition.
+ * One query row of one (image, head): the plain definition, on inputs already decoded to double.
  *   S_j = scale * sum_d q[d] k_j[d]          j in [0, n)
  *   M   = max_j S_j ; p_j = exp(S_j - M) ; L = sum_j p_j
  *   o[d] = (sum_j p_j v_j[d]) / L
  * Subtracting M is the usual overflow guard; it cancels in p_j / L.
  * probs (optional, length n) receives p_j / L.
  */
-static void attend_row(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
+static void attend_row(const double *q, const double *k, const double *v,
                        int64_t s, int n, int r, int h, int H, int D, double scale,
                        double *scores, double *o, double *probs)
 {
-    const int64_t tok = (int64_t)H * D;            /* words between consecutive tokens */
-    const uint16_t *qrow = q + (s + r) * tok + (int64_t)h * D;
+    const int64_t tok = (int64_t)H * D;            /* elements between consecutive tokens */
+    const double *qrow = q + (s + r) * tok + (int64_t)h * D;
     double M = -INFINITY;
     for (int j = 0; j < n; ++j) {
-        const uint16_t *krow = k + (s + j) * tok + (int64_t)h * D;
+        const double *krow = k + (s + j) * tok + (int64_t)h * D;
         double dot = 0.0;
-        for (int d = 0; d < D; ++d) dot += decode(qrow[d], dtype) * decode(krow[d], dtype);
+        for (int d = 0; d < D; ++d) dot += qrow[d] * krow[d];
         scores[j] = scale * dot;
         if (scores[j] > M) M = scores[j];
     }
@@ -159,19 +159,28 @@ static void attend_row(const uint16_t *q, const uint16_t *k, const uint16_t *v, 
     }
     for (int d = 0; d < D; ++d) o[d] = 0.0;
     for (int j = 0; j < n; ++j) {
-        const uint16_t *vrow = v + (s + j) * tok + (int64_t)h * D;
-        for (int d = 0; d < D; ++d) o[d] += scores[j] * decode(vrow[d], dtype);
+        const double *vrow = v + (s + j) * tok + (int64_t)h * D;
+        for (int d = 0; d < D; ++d) o[d] += scores[j] * vrow[d];
     }
     for (int d = 0; d < D; ++d) o[d] /= L;
     if (probs) for (int j = 0; j < n; ++j) probs[j] = scores[j] / L;
 }
 
+/* Decode rows [0, rows) of a [rows, H*D] 16-bit buffer to a freshly allocated double buffer. */
+static double *decode_all(const uint16_t *w, int64_t count, int dtype)
+{
+    double *out = (double *)malloc((size_t)(count > 0 ? count : 1) * sizeof(double));
+    if (out) for (int64_t e = 0; e < count; ++e) out[e] = decode(w[e], dtype);
+    return out;
+}
+
 /*
  * Ragged attention (Section 4.2): q, k, v are [T, H, D] 16-bit words (token-major, then head,
  * then head-dim), out is [T, H, D] doubles.  Image i owns rows [cu[i], cu[i+1]).
- * threads <= 1 runs serially; otherwise (image, head) pairs are spread over that many OpenMP
- * threads -- the arithmetic of every row is unchanged.  Returns 0, or -1 if scratch allocation
- * failed.
+ * The inputs are first decoded exactly to double; then every (image, head, row) is evaluated by
+ * the definition above.  threads <= 1 runs serially; otherwise (image, head) pairs are spread
+ * over that many OpenMP threads -- the arithmetic of every row is unchanged.
+ * Returns 0, or -1 if an allocation failed.
  */
 int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
                 const int32_t *cu_seqlens, int B, int H, int D, float scale,
@@ -184,8 +193,12 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dty
     }
     if (nmax == 0) return 0;
     if (threads < 1) threads = 1;
-    int failed = 0;
-    const int pairs = B * H;
+    const int64_t count = (int64_t)cu_seqlens[B] * H * D;
+    double *qd = decode_all(q, count, dtype);
+    double *kd = decode_all(k, count, dtype);
+    double *vd = decode_all(v, count, dtype);
+    int failed = !qd || !kd || !vd;
+    const int pairs = failed ? 0 : B * H;
 #ifdef _OPENMP
 #pragma omp parallel num_threads(threads)
 #endif
@@ -207,17 +220,19 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dty
             int n = cu_seqlens[i + 1] - cu_seqlens[i];
             for (int r = 0; r < n; ++r) {
                 double *o = out + ((s + r) * (int64_t)H + h) * D;
-                attend_row(q, k, v, dtype, s, n, r, h, H, D, (double)scale, scores, o, NULL);
+                attend_row(qd, kd, vd, s, n, r, h, H, D, (double)scale, scores, o, NULL);
             }
         }
         free(scores);
     }
+    free(qd); free(kd); free(vd);
     return failed ? -1 : 0;
 }
 
 /*
- * Debug view for the "softmax rows sum to one" invariant: the normalised probabilities p_j / L
- * of query row r of image i, head h (length n_i), plus that row's output.
+ * Debug view for the "softmax rows sum to one" invariant, also used to check sampled rows of
+ * large batches: the normalised probabilities p_j / L of query row r of image i, head h
+ * (length n_i), plus that row's output.  Decodes only that image's rows.
  */
 int oracle_attn_row(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
                     const int32_t *cu_seqlens, int i, int h, int r, int H, int D, float scale,
@@ -226,11 +241,15 @@ int oracle_attn_row(const uint16_t *q, const uint16_t *k, const uint16_t *v, int
     int64_t s = cu_seqlens[i];
     int n = cu_seqlens[i + 1] - cu_seqlens[i];
     if (r < 0 || r >= n) return -1;
+    const int64_t tok = (int64_t)H * D;
     double *scores = (double *)malloc((size_t)n * sizeof(double));
-    if (!scores) return -1;
-    attend_row(q, k, v, dtype, s, n, r, h, H, D, (double)scale, scores, o, probs);
-    free(scores);
-    return 0;
+    double *qd = decode_all(q + s * tok, (int64_t)n * tok, dtype);
+    double *kd = decode_all(k + s * tok, (int64_t)n * tok, dtype);
+    double *vd = decode_all(v + s * tok, (int64_t)n * tok, dtype);
+    int ok = scores && qd && kd && vd;
+    if (ok) attend_row(qd, kd, vd, 0, n, r, h, H, D, (double)scale, scores, o, probs);
+    free(scores); free(qd); free(kd); free(vd);
+    return ok ? 0 : -1;
 }
 
 /* Number of OpenMP threads a parallel region would get by default (1 without OpenMP). */

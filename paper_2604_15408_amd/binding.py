@@ -1,0 +1,133 @@
+"""ctypes binding of the C ABI in ``include/ragged.h`` (argument marshalling only).
+
+Every function takes torch tensors that already live on the GPU, checks shapes/dtypes/contiguity,
+passes raw device pointers and the current HIP stream to the library and returns at once; all
+computation happens in the HIP kernels.  There is no CPU fallback: if the shared library has not
+been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libragged_hip.so"
+
+RAGGED_OK = 0
+RAGGED_F16, RAGGED_BF16, RAGGED_F32 = 0, 1, 2
+_DTYPE_CODE = {torch.float16: RAGGED_F16, torch.bfloat16: RAGGED_BF16, torch.float32: RAGGED_F32}
+
+EXPORTS = ("ragged_pack", "ragged_attn", "ragged_unpack", "ragged_noop", "ragged_status_string",
+           "ragged_version")
+
+_lib = None
+
+
+class RaggedError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed with status {status}: {status_string(status)}")
+
+
+def load() -> ctypes.CDLL:
+    """Open the in-tree shared library (built by ``paper_2604_15408_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2604_15408_amd.build` "
+                "(there is no fallback implementation)")
+        lib = ctypes.CDLL(str(LIB_PATH))
+        vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float
+        lib.ragged_pack.argtypes = [vp, vp, i32, i32, i32, i32, vp, i64, vp, vp, vp]
+        lib.ragged_pack.restype = i32
+        lib.ragged_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, vp]
+        lib.ragged_attn.restype = i32
+        lib.ragged_unpack.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
+        lib.ragged_unpack.restype = i32
+        lib.ragged_noop.argtypes = [i32, vp]
+        lib.ragged_noop.restype = i32
+        lib.ragged_status_string.argtypes = [i32]
+        lib.ragged_status_string.restype = ctypes.c_char_p
+        lib.ragged_version.argtypes = []
+        lib.ragged_version.restype = i32
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().ragged_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load().ragged_version())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, name: str, dtype=None, shape=None) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise TypeError(f"{name} has dtype {t.dtype}, expected {dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t.data_ptr()
+
+
+def _check(fn: str, status: int) -> None:
+    if status != RAGGED_OK:
+        raise RaggedError(fn, status)
+
+
+def ragged_pack(x, keep, packed, cu_seqlens, gather_idx, stream=None) -> None:
+    """x [B,N,C] f16/bf16, keep [B,N] uint8/bool -> packed [cap,C], cu_seqlens [B+1] i32,
+    gather_idx [cap] i32 (all caller-allocated; cap = packed.shape[0])."""
+    B, N, C = x.shape
+    cap = packed.shape[0]
+    st = load().ragged_pack(
+        _dev(x, "x", (torch.float16, torch.bfloat16)),
+        _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)), B, N, C, _DTYPE_CODE[x.dtype],
+        _dev(packed, "packed", x.dtype, (cap, C)), cap,
+        _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
+        _dev(gather_idx, "gather_idx", torch.int32, (cap,)), _stream(stream))
+    _check("ragged_pack", st)
+
+
+def ragged_attn(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=None) -> None:
+    """q,k,v [rows,H,D] f16/bf16 and o [rows,H,D] (same dtype or f32); only rows < cu_seqlens[-1]
+    are read / written."""
+    rows, H, D = q.shape
+    B = cu_seqlens.shape[0] - 1
+    st = load().ragged_attn(
+        _dev(q, "q", (torch.float16, torch.bfloat16)), _dev(k, "k", q.dtype, q.shape),
+        _dev(v, "v", q.dtype, q.shape), _dev(o, "o", (q.dtype, torch.float32), q.shape),
+        _dev(cu_seqlens, "cu_seqlens", torch.int32), B, int(max_seqlen), H, D, float(scale),
+        _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], _stream(stream))
+    _check("ragged_attn", st)
+
+
+def ragged_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> None:
+    """src [rows,C] -> out [B,N,C].  fill_mode 0 needs gather_idx (keep may be None); fill_mode 1
+    needs keep (gather_idx may be None)."""
+    B, N, C = out.shape
+    st = load().ragged_unpack(
+        _dev(src, "src", (torch.float16, torch.bfloat16)),
+        None if keep is None else _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)),
+        _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
+        None if gather_idx is None else _dev(gather_idx, "gather_idx", torch.int32),
+        B, N, C, _DTYPE_CODE[src.dtype], _dev(out, "out", src.dtype), int(fill_mode),
+        _stream(stream))
+    _check("ragged_unpack", st)
+
+
+def ragged_noop(grid: int, stream=None) -> None:
+    _check("ragged_noop", load().ragged_noop(int(grid), _stream(stream)))

@@ -1,0 +1,64 @@
+"""Build the gfx950 shared library in-tree with hipcc (cross-compiles without a GPU).
+
+    python -m paper_2604_15408_amd.build            # build libragged_hip.so next to this file
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+from pathlib import Path
+
+PKG = Path(__file__).resolve().parent
+ROOT = PKG.parent
+CSRC = PKG / "csrc"
+LIB = PKG / "libragged_hip.so"
+BUILD_DIR = PKG / "_build"
+SOURCES = ["ragged_api.hip", "pack_unpack.hip", "attn.hip"]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+    # never let the compiler form packed-fp32 VALU ops (unreliable on this target)
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    f"-I{ROOT / 'include'}", f"-I{CSRC}",
+]
+
+
+def _hipcc() -> str:
+    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if cand and (os.path.sep not in cand or os.path.exists(cand)):
+            return cand
+    raise RuntimeError("hipcc not found")
+
+
+def build(verbose: bool = False, extra_flags=()) -> Path:
+    """Compile every HIP source for gfx950 and link the C-ABI shared library.  Always recompiles."""
+    BUILD_DIR.mkdir(exist_ok=True)
+    hipcc = _hipcc()
+
+    def compile_one(name: str) -> Path:
+        obj = BUILD_DIR / (name + ".o")
+        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-c", str(CSRC / name), "-o", str(obj)]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        noise = "is not a recognized feature for this target"
+        err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {name}:\n{err}")
+        if verbose and err.strip():
+            print(err, file=sys.stderr)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    tmp = LIB.with_suffix(f".tmp{os.getpid()}.so")
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp),
+                          *map(str, objs)], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"link failed:\n{res.stderr}")
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,314 @@
+// Bidirectional multi-head attention over a packed ragged buffer (Section 4.2, Algorithm 1), for
+// gfx950: one launch, one work-group per (image, head, 64-query tile), K/V tiles staged in LDS,
+// MFMA 16x16x32 for both contractions with fp32 accumulation, fp32 online softmax.
+//
+// Orientation.  Each wavefront owns 16 queries and computes the TRANSPOSED score tile
+// S^T = K Q^T (keys x queries).  In the MFMA result layout a lane then holds, for ONE query
+// (column lane%16), the scores of keys 4*(lane/16)+r of every 16-key tile.  That is already the
+// "B operand" shape of the second contraction O^T = V^T P^T, so P never leaves registers, the
+// softmax statistics are per-lane scalars, and a row maximum needs only two cross-lane steps
+// (lanes l, l^16, l^32, l^48 share a query).
+//
+// MFMA 16x16x32 operand layout used below (A: 16 rows x 32 k, B: 32 k x 16 cols, D: 16x16):
+//   A: lane l holds row l%16,  k-slots 8*(l/16)+e, e = 0..7
+//   B: lane l holds col l%16,  k-slots 8*(l/16)+e
+//   D: lane l, register r holds row 4*(l/16)+r, col l%16
+// Which contraction index sits in which k-slot is free as long as A and B agree, and which logical
+// row/column an MFMA row/column stands for is free as long as loads and stores agree.  Both
+// freedoms are used to make every LDS access a conflict-free 16-byte one and every global access a
+// contiguous 32 bytes per lane:
+//   * Q (B operand of S^T): lane group g = l/16 loads head-dim elements 16g..16g+15 of its query.
+//   * K tile in LDS, row-major [key][d], row stride 72 halves; A operand = 8 halves at d = 16g+8s.
+//   * V tile in LDS TRANSPOSED, [rho][kappa], stride 72 halves, where
+//        rho(d)     = (d%4)*16 + d/4                      (row permutation of the head dim)
+//        kappa(key) = 32*(key/32) + 8*((key%16)/4) + 4*((key%32)/16) + key%4
+//     so that lane group g reads 8 consecutive kappa = exactly the keys whose probabilities it
+//     holds, and ends up owning output elements d = 16g .. 16g+15 of its query (32 contiguous
+//     bytes).  The transposition is done once per tile in registers while filling LDS.
+//
+// bf16 inputs: Q K^T uses the bf16 MFMA (products are exact in fp32).  A bf16 probability would
+// carry only 8 significant bits, so P is split as P = P_hi + P_lo (two bf16 values, 16 bits
+// together) and P V is two MFMAs; V stays exact.  The path is not MFMA-bound at ViT lengths.
+#include "common.h"
+
+namespace ragged {
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kHeadDim = 64;
+constexpr int kBM = 64;                 // queries per work-group (16 per wavefront)
+constexpr int kBN = 64;                 // keys per K/V tile
+constexpr int kLdsStride = 72;          // halves per LDS row: 64 + 8 of padding (144 bytes)
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct F16 {
+    typedef f16x8 vec8;
+    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
+struct BF16 {
+    typedef bf16x8 vec8;
+    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+template <typename V>
+__device__ __forceinline__ V as_vec8(uint4 raw) { return __builtin_bit_cast(V, raw); }
+
+// O^T += V^T P^T for one 32-key block: p[0..7] are this lane's probabilities (fp32).
+__device__ __forceinline__ void pv_block(F16, const uint4 (&vt)[4], const float (&p)[8], f32x4 (&o)[4]) {
+    f16x8 pb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[e];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) o[dt] = F16::mfma(as_vec8<f16x8>(vt[dt]), pb, o[dt]);
+}
+__device__ __forceinline__ void pv_block(BF16, const uint4 (&vt)[4], const float (&p)[8], f32x4 (&o)[4]) {
+    bf16x8 hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        hi[e] = (__bf16)p[e];
+        lo[e] = (__bf16)(p[e] - (float)hi[e]);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        o[dt] = BF16::mfma(as_vec8<bf16x8>(vt[dt]), hi, o[dt]);
+        o[dt] = BF16::mfma(as_vec8<bf16x8>(vt[dt]), lo, o[dt]);
+    }
+}
+
+// Store 16 consecutive head-dim elements of one output row.
+__device__ __forceinline__ void store16(_Float16* dst, const float (&v)[16]) {
+    f16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (_Float16)v[e]; b[e] = (_Float16)v[8 + e]; }
+    reinterpret_cast<uint4*>(dst)[0] = __builtin_bit_cast(uint4, a);
+    reinterpret_cast<uint4*>(dst)[1] = __builtin_bit_cast(uint4, b);
+}
+__device__ __forceinline__ void store16(__bf16* dst, const float (&v)[16]) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)v[e]; b[e] = (__bf16)v[8 + e]; }
+    reinterpret_cast<uint4*>(dst)[0] = __builtin_bit_cast(uint4, a);
+    reinterpret_cast<uint4*>(dst)[1] = __builtin_bit_cast(uint4, b);
+}
+__device__ __forceinline__ void store16(float* dst, const float (&v)[16]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        reinterpret_cast<float4*>(dst)[e] = make_float4(v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]);
+}
+
+// Work-group index -> logical work item.  The hardware deals consecutive work-groups round-robin
+// to the 8 XCDs (each with its own L2).  Giving XCD x the contiguous slice [x*per, (x+1)*per) of
+// logical items keeps the q-tiles of one (image, head) -- which re-read the same K/V -- and the
+// heads of one image on one L2.
+__device__ __forceinline__ int logical_item(int bid, int per_xcd) {
+    return (bid % kXcds) * per_xcd + bid / kXcds;
+}
+
+template <typename In, typename OutT>
+__global__ __launch_bounds__(kBlockThreads)
+void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                 const uint16_t* __restrict__ v, OutT* __restrict__ o,
+                 const int32_t* __restrict__ cu_seqlens, int H, int q_tiles, int items,
+                 int per_xcd, float scale_log2e) {
+    typedef typename In::vec8 vec8;
+    __shared__ __attribute__((aligned(16))) uint16_t k_lds[kBN * kLdsStride];
+    __shared__ __attribute__((aligned(16))) uint16_t vt_lds[kHeadDim * kLdsStride];
+
+    const int item = logical_item(blockIdx.x, per_xcd);
+    if (item >= items) return;
+    const int m_tile = item % q_tiles;
+    const int pair = item / q_tiles;
+    const int h = pair % H;
+    const int img = pair / H;
+    const int s = cu_seqlens[img];
+    const int n = cu_seqlens[img + 1] - s;
+    const int m0 = m_tile * kBM;
+    if (m0 >= n) return;                                       // whole group exits together
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = tid >> 6;
+    const int col = lane & 15;                                 // query inside the wavefront's 16
+    const int g = lane >> 4;                                   // lane group
+    const int64_t tok = (int64_t)H * kHeadDim;                 // elements between tokens
+    const int64_t head_off = (int64_t)h * kHeadDim;
+
+    // ---- Q: this lane's query row, head-dim elements 16g .. 16g+15 (zeros past the sequence end)
+    const int q_row = m0 + wave * 16 + col;
+    uint4 q_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+    if (q_row < n) {
+        const uint4* src = reinterpret_cast<const uint4*>(q + (s + q_row) * tok + head_off + 16 * g);
+        q_raw[0] = src[0];
+        q_raw[1] = src[1];
+    }
+    const vec8 q_frag[2] = {as_vec8<vec8>(q_raw[0]), as_vec8<vec8>(q_raw[1])};
+
+    // ---- tile-fill roles: wavefronts 0-1 copy K (4 x 16 B each), wavefronts 2-3 transpose V
+    const int fill = tid & 127;
+    const int fill_dc = fill & 7;                              // which 8-element slice of the head dim
+    const int fill_kg = fill >> 3;                             // K: key = fill_kg + 16*a ; V: keys 4*fill_kg + a
+    const bool fills_k = tid < 128;
+
+    float m_run = -INFINITY;                                   // running max (log2 domain)
+    float l_run = 0.f;                                         // running sum, this lane's keys only
+    f32x4 o_acc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) o_acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int j0 = 0; j0 < n; j0 += kBN) {
+        const int rem = n - j0;                                // valid keys in this tile (>= 1)
+        // -------- global -> registers
+        uint4 raw[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int key = fills_k ? fill_kg + 16 * a : 4 * fill_kg + a;
+            raw[a] = make_uint4(0, 0, 0, 0);
+            if (key < rem) {
+                const uint16_t* base = fills_k ? k : v;
+                raw[a] = *reinterpret_cast<const uint4*>(base + (s + j0 + key) * tok + head_off + 8 * fill_dc);
+            }
+        }
+        if (j0 > 0) __syncthreads();                           // previous tile fully consumed
+        // -------- registers -> LDS
+        if (fills_k) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const int key = fill_kg + 16 * a;
+                *reinterpret_cast<uint4*>(&k_lds[key * kLdsStride + 8 * fill_dc]) = raw[a];
+            }
+        } else {
+            // keys 4*fill_kg .. +3 occupy 4 consecutive kappa slots
+            const int key0 = 4 * fill_kg;
+            const int kappa = 32 * (key0 >> 5) + 8 * ((key0 & 15) >> 2) + 4 * ((key0 & 31) >> 4);
+            const uint32_t w[4][4] = {{raw[0].x, raw[0].y, raw[0].z, raw[0].w},
+                                      {raw[1].x, raw[1].y, raw[1].z, raw[1].w},
+                                      {raw[2].x, raw[2].y, raw[2].z, raw[2].w},
+                                      {raw[3].x, raw[3].y, raw[3].z, raw[3].w}};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int d = 8 * fill_dc + e;
+                const int rho = (d & 3) * 16 + (d >> 2);
+                uint2 packed4;
+                if (e & 1) {
+                    packed4.x = (w[0][e >> 1] >> 16) | (w[1][e >> 1] & 0xffff0000u);
+                    packed4.y = (w[2][e >> 1] >> 16) | (w[3][e >> 1] & 0xffff0000u);
+                } else {
+                    packed4.x = (w[0][e >> 1] & 0xffffu) | (w[1][e >> 1] << 16);
+                    packed4.y = (w[2][e >> 1] & 0xffffu) | (w[3][e >> 1] << 16);
+                }
+                *reinterpret_cast<uint2*>(&vt_lds[rho * kLdsStride + kappa]) = packed4;
+            }
+        }
+        __syncthreads();
+
+        // -------- S^T = K Q^T : four 16-key tiles, two k-steps of 32 head-dim elements
+        f32x4 st[4];
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (16 * kt < rem) {
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const uint4 a = *reinterpret_cast<const uint4*>(
+                        &k_lds[(16 * kt + col) * kLdsStride + 16 * g + 8 * ks]);
+                    st[kt] = In::mfma(as_vec8<vec8>(a), q_frag[ks], st[kt]);
+                }
+            }
+        }
+
+        // -------- online softmax (this lane: one query, keys j0 + 16*kt + 4*g + r)
+        float t_max = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float sc = (16 * kt + 4 * g + r < rem) ? st[kt][r] * scale_log2e : -INFINITY;
+                st[kt][r] = sc;
+                t_max = fmaxf(t_max, sc);
+            }
+        t_max = fmaxf(t_max, __shfl_xor(t_max, 16, kWaveSize));
+        t_max = fmaxf(t_max, __shfl_xor(t_max, 32, kWaveSize));
+        const float m_new = fmaxf(m_run, t_max);               // finite: the tile has a valid key
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float t_sum = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = __builtin_amdgcn_exp2f(st[kt][r] - m_new);
+                st[kt][r] = p;
+                t_sum += p;
+            }
+        l_run = l_run * alpha + t_sum;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) o_acc[dt] *= alpha;
+
+        // -------- O^T += V^T P^T : two 32-key blocks x four 16-row head-dim tiles
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb) {
+            if (32 * bb < rem) {
+                uint4 vt[4];
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+                    vt[dt] = *reinterpret_cast<const uint4*>(
+                        &vt_lds[(16 * dt + col) * kLdsStride + 32 * bb + 8 * g]);
+                const float p[8] = {st[2 * bb][0], st[2 * bb][1], st[2 * bb][2], st[2 * bb][3],
+                                    st[2 * bb + 1][0], st[2 * bb + 1][1], st[2 * bb + 1][2], st[2 * bb + 1][3]};
+                pv_block(In{}, vt, p, o_acc);
+            }
+        }
+    }
+
+    // ---- normalise and store: this lane owns d = 16g + 4r + dt of its query
+    float l_tot = l_run + __shfl_xor(l_run, 16, kWaveSize);
+    l_tot += __shfl_xor(l_tot, 32, kWaveSize);
+    if (q_row < n) {
+        const float inv = 1.0f / l_tot;
+        float out16[16];
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out16[4 * r + dt] = o_acc[dt][r] * inv;
+        store16(o + (s + q_row) * tok + head_off + 16 * g, out16);
+    }
+}
+
+template <typename In, typename OutT>
+hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
+                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
+                        hipStream_t stream) {
+    const int q_tiles = (max_seqlen + kBM - 1) / kBM;
+    const int items = B * H * q_tiles;
+    const int per_xcd = (items + kXcds - 1) / kXcds;
+    hipLaunchKernelGGL((attn_kernel<In, OutT>), dim3(per_xcd * kXcds), dim3(kBlockThreads), 0, stream,
+                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                       static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, H,
+                       q_tiles, items, per_xcd, scale * kLog2e);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
+                       const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
+                       ragged_dtype in_dt, ragged_dtype out_dt, hipStream_t stream) {
+    if (in_dt == RAGGED_F16 && out_dt == RAGGED_F16)
+        return launch_typed<F16, _Float16>(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, stream);
+    if (in_dt == RAGGED_F16 && out_dt == RAGGED_F32)
+        return launch_typed<F16, float>(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, stream);
+    if (in_dt == RAGGED_BF16 && out_dt == RAGGED_BF16)
+        return launch_typed<BF16, __bf16>(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, stream);
+    if (in_dt == RAGGED_BF16 && out_dt == RAGGED_F32)
+        return launch_typed<BF16, float>(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace ragged

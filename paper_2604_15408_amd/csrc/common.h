@@ -1,0 +1,38 @@
+// Shared host/device declarations of the gfx950 ragged-attention library (internal; the public
+// interface is include/ragged.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ragged.h"
+
+namespace ragged {
+
+constexpr int kWaveSize = 64;          // CDNA wavefront width
+constexpr int kBlockThreads = 256;     // 4 wavefronts per work-group in every kernel here
+constexpr int kXcds = 8;               // MI355X: 8 accelerator dies, work-groups dealt round-robin
+
+// Host launchers (one kernel each).  All arguments have been validated by the C ABI layer.
+hipError_t launch_pack(const void* x, const uint8_t* keep, int B, int N, int C, void* packed,
+                       int64_t cap_rows, int32_t* cu_seqlens, int32_t* gather_idx,
+                       hipStream_t stream);
+hipError_t launch_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlens,
+                         const int32_t* gather_idx, int B, int N, int C, void* out, int fill_mode,
+                         hipStream_t stream);
+hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
+                       const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
+                       ragged_dtype in_dt, ragged_dtype out_dt, hipStream_t stream);
+hipError_t launch_noop(int grid, hipStream_t stream);
+
+// Tokens of one image handled by one work-group of the pack / zero-filling unpack kernels.
+// Small chunks expose more parallelism (the copies are latency-bound at ViT sizes); the chunk
+// grows once the grid would exceed what the 256 CUs can hold resident.
+inline int pick_chunk(int B, int N) {
+    const int64_t tokens = (int64_t)B * N;
+    int chunk = 8;
+    while (chunk < 64 && tokens / chunk > 4096) chunk *= 2;
+    return chunk;
+}
+
+}  // namespace ragged

@@ -1,0 +1,83 @@
+// C ABI of the library (declared in include/ragged.h): argument validation on the host, then
+// exactly one kernel launch per call.  No allocation, no synchronisation, no host read-back, so
+// every entry point may be recorded into a HIP graph.
+#include <math.h>
+
+#include "common.h"
+
+namespace {
+
+constexpr int kVersion = 100;  // 0.1.0
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_BF16; }
+
+// B*N rows must be indexable with int32 (gather_idx and cu_seqlens are int32).
+inline bool rows_fit(int B, int N) { return (int64_t)B * N <= (int64_t)INT32_MAX; }
+
+inline int from_hip(hipError_t e) { return e == hipSuccess ? RAGGED_OK : RAGGED_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int ragged_pack(const void* x, const uint8_t* keep, int B, int N, int C, ragged_dtype dt,
+                void* packed, int64_t cap_rows, int32_t* cu_seqlens, int32_t* gather_idx,
+                void* stream) {
+    if (!x || !keep || !packed || !cu_seqlens || !gather_idx) return RAGGED_ERR_NULL;
+    if (B <= 0 || N <= 0 || C <= 0 || !rows_fit(B, N)) return RAGGED_ERR_SHAPE;
+    if (!is16bit(dt) || (C & 7) != 0 || !aligned16(x) || !aligned16(packed)) return RAGGED_ERR_UNSUPPORTED;
+    if (cap_rows < 1) return RAGGED_ERR_CAPACITY;
+    return from_hip(ragged::launch_pack(x, keep, B, N, C, packed, cap_rows, cu_seqlens, gather_idx,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int ragged_attn(const void* q, const void* k, const void* v, void* o,
+                const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
+                float scale, ragged_dtype in_dt, ragged_dtype out_dt, void* stream) {
+    if (!q || !k || !v || !o || !cu_seqlens) return RAGGED_ERR_NULL;
+    if (B <= 0 || H <= 0 || D <= 0 || max_seqlen < 1) return RAGGED_ERR_SHAPE;
+    const int64_t items = (int64_t)B * H * (((int64_t)max_seqlen + 63) / 64);
+    if (items + 8 > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
+    if (D != 64) return RAGGED_ERR_UNSUPPORTED;
+    const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
+                         (in_dt == RAGGED_BF16 && (out_dt == RAGGED_BF16 || out_dt == RAGGED_F32));
+    if (!pair_ok || !isfinite(scale)) return RAGGED_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_attn(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, in_dt, out_dt,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int ragged_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlens,
+                  const int32_t* gather_idx, int B, int N, int C, ragged_dtype dt,
+                  void* out, int fill_mode, void* stream) {
+    if (fill_mode != 0 && fill_mode != 1) return RAGGED_ERR_UNSUPPORTED;
+    if (!src || !cu_seqlens || !out) return RAGGED_ERR_NULL;
+    if (fill_mode == 0 && !gather_idx) return RAGGED_ERR_NULL;
+    if (fill_mode == 1 && !keep) return RAGGED_ERR_NULL;
+    if (B <= 0 || N <= 0 || C <= 0 || !rows_fit(B, N)) return RAGGED_ERR_SHAPE;
+    if (!is16bit(dt) || (C & 7) != 0 || !aligned16(src) || !aligned16(out)) return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_unpack(src, keep, cu_seqlens, gather_idx, B, N, C, out, fill_mode,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+int ragged_noop(int grid, void* stream) {
+    if (grid < 1) return RAGGED_ERR_SHAPE;
+    return from_hip(ragged::launch_noop(grid, static_cast<hipStream_t>(stream)));
+}
+
+const char* ragged_status_string(int status) {
+    switch (status) {
+        case RAGGED_OK: return "ok";
+        case RAGGED_ERR_NULL: return "a required pointer is NULL";
+        case RAGGED_ERR_SHAPE: return "a dimension is non-positive or too large";
+        case RAGGED_ERR_UNSUPPORTED: return "unsupported dtype, head dim, alignment, scale or fill mode";
+        case RAGGED_ERR_CAPACITY: return "cap_rows must be at least 1";
+        case RAGGED_ERR_HIP: return "the HIP runtime refused the launch";
+        default: return "unknown";
+    }
+}
+
+int ragged_version(void) { return kVersion; }
+
+}  // extern "C"

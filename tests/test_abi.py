@@ -1,0 +1,95 @@
+"""Host-side checks of the C ABI that need no GPU: the shared library loads, exports every symbol
+the header declares, and rejects bad arguments with the documented status before any launch."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2604_15408_amd import binding
+
+ROOT = Path(__file__).resolve().parents[1]
+FAKE = 0x10000          # non-null, 16-byte aligned; never dereferenced because validation fails first
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not binding.LIB_PATH.exists():
+        from paper_2604_15408_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = (ROOT / "include" / "ragged.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ragged_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert binding.version() >= 100
+    assert binding.status_string(0) == "ok"
+    texts = {binding.status_string(s) for s in range(6)}
+    assert len(texts) == 6 and binding.status_string(99) == "unknown"
+
+
+def _pack(lib, x=FAKE, keep=FAKE, B=2, N=8, C=64, dt=0, packed=FAKE, cap=16, cu=FAKE, gi=FAKE):
+    return lib.ragged_pack(x, keep, B, N, C, dt, packed, cap, cu, gi, None)
+
+
+def _attn(lib, q=FAKE, k=FAKE, v=FAKE, o=FAKE, cu=FAKE, B=2, ms=8, H=2, D=64, scale=0.125, i=0, od=0):
+    return lib.ragged_attn(q, k, v, o, cu, B, ms, H, D, scale, i, od, None)
+
+
+def _unpack(lib, src=FAKE, keep=FAKE, cu=FAKE, gi=FAKE, B=2, N=8, C=64, dt=0, out=FAKE, fm=0):
+    return lib.ragged_unpack(src, keep, cu, gi, B, N, C, dt, out, fm, None)
+
+
+def test_pack_validation(lib):
+    for null in ("x", "keep", "packed", "cu", "gi"):
+        assert _pack(lib, **{null: None}) == 1
+    for bad in (dict(B=0), dict(N=-1), dict(C=0), dict(B=1 << 20, N=1 << 20)):
+        assert _pack(lib, **bad) == 2
+    for bad in (dict(dt=2), dict(dt=7), dict(C=12), dict(x=FAKE + 2), dict(packed=FAKE + 8)):
+        assert _pack(lib, **bad) == 3
+    assert _pack(lib, cap=0) == 4
+
+
+def test_attn_validation(lib):
+    for null in ("q", "k", "v", "o", "cu"):
+        assert _attn(lib, **{null: None}) == 1
+    for bad in (dict(B=0), dict(H=0), dict(D=0), dict(ms=0), dict(B=1 << 30, H=64)):
+        assert _attn(lib, **bad) == 2
+    for bad in (dict(D=48), dict(i=2), dict(i=0, od=1), dict(i=1, od=0), dict(scale=float("inf")),
+                dict(scale=float("nan")), dict(q=FAKE + 4), dict(o=FAKE + 8)):
+        assert _attn(lib, **bad) == 3
+
+
+def test_unpack_validation(lib):
+    assert _unpack(lib, fm=2) == 3
+    for null in ("src", "cu", "out"):
+        assert _unpack(lib, **{null: None}) == 1
+    assert _unpack(lib, gi=None, fm=0) == 1 and _unpack(lib, keep=None, fm=1) == 1
+    for bad in (dict(B=0), dict(N=0), dict(C=-8)):
+        assert _unpack(lib, **bad) == 2
+    for bad in (dict(dt=2), dict(C=20), dict(src=FAKE + 1), dict(out=FAKE + 2)):
+        assert _unpack(lib, **bad) == 3
+
+
+def test_noop_validation(lib):
+    assert lib.ragged_noop(0, None) == 2
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 4, 64, dtype=torch.float16)
+    with pytest.raises(TypeError):
+        binding.ragged_pack(x, torch.ones(1, 4, dtype=torch.uint8), torch.zeros(4, 64, dtype=torch.float16),
+                            torch.zeros(2, dtype=torch.int32), torch.zeros(4, dtype=torch.int32), stream=0)

@@ -1,0 +1,203 @@
+"""GPU parity of ragged_attn against the fp64 CPU oracle.
+
+Bar: max-abs-error <= 2e-3 on N(0,1) inputs (fp16 in/out, fp16->fp32, bf16->fp32).  With bf16
+OUTPUT the final rounding alone is up to half a bf16 ulp = 2^-9 * 2^floor(log2|o|) <= 2^-8 * |o|,
+so that case is held to 2e-3 + 2^-8 * |oracle|.  Several outputs are correct (the reduction order
+is free), so the comparison is a tolerance, never bit equality -- except where the mathematics
+fixes the bits (n = 1, ragged isolation, run-to-run determinism, untouched rows).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_15408_amd import workloads as wl
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+_TD = {"f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def _qkv(T, H, dtype, seed, D=64):
+    g = torch.Generator().manual_seed(seed)
+    return tuple(torch.randn(T, H, D, generator=g, dtype=torch.float32).to(_TD[dtype]) for _ in range(3))
+
+
+def check(lengths, H, dtype, seed, scale=0.125, out_dtype=None, max_seqlen=None, tol=TOL):
+    cu = hp.cu_from_lengths(lengths)
+    T = int(cu[-1])
+    q, k, v = _qkv(T, H, dtype, seed)
+    want = oracle.attn(wl.to_words(q), wl.to_words(k), wl.to_words(v), cu, scale, dtype, threads=8)
+    ms = max(max(lengths), 1) if max_seqlen is None else max_seqlen
+    got, raw = hp.gpu_attn(q, k, v, cu, ms, scale, out_dtype, extra_rows=3)
+    assert np.all(raw[T:].to(torch.float64).numpy() == 77.0), "rows past T were written"
+    assert np.all(np.isfinite(got[:T]))
+    err = np.abs(got[:T] - want)
+    bound = tol + (np.abs(want) * 2.0 ** -8 if raw.dtype == torch.bfloat16 else 0.0)
+    assert np.all(err <= bound), f"max abs err {err.max():.3e} (lengths={lengths[:8]}..)"
+    return float(err.max()) if T else 0.0
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 15, 16, 17, 31, 32, 33, 40, 47, 48, 49, 63, 64, 65, 100, 127, 128,
+                               129, 191, 192, 193, 197, 255, 256, 257, 300, 577])
+def test_single_sequence_lengths_fp16(n):
+    check([n], 2, "f16", 100 + n)
+
+
+@pytest.mark.parametrize("n", [1, 2, 17, 40, 64, 65, 197, 577])
+@pytest.mark.parametrize("out", ["same", "f32"])
+def test_single_sequence_lengths_bf16(n, out):
+    check([n], 2, "bf16", 200 + n, out_dtype=torch.float32 if out == "f32" else None)
+
+
+@pytest.mark.parametrize("n", [1, 40, 65, 197])
+def test_fp16_in_fp32_out(n):
+    check([n, 3, n], 3, "f16", 300 + n, out_dtype=torch.float32)
+
+
+def test_tiny_workload():
+    w = wl.tiny()
+    q, k, v = w.qkv()
+    cu = hp.cu_from_lengths(w.lengths)
+    want = oracle.attn(wl.to_words(q), wl.to_words(k), wl.to_words(v), cu, w.scale, "f16", threads=8)
+    got, _ = hp.gpu_attn(q, k, v, cu, w.N, w.scale)
+    assert np.max(np.abs(got - want)) <= TOL
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_ragged_batches_with_empty_and_single_token_images(seed):
+    rng = np.random.default_rng(seed)
+    lengths = [int(v) for v in rng.integers(0, 200, size=12)]
+    lengths[rng.integers(12)] = 0
+    lengths[rng.integers(12)] = 1
+    lengths[0] = 0 if seed % 2 else lengths[0]
+    lengths[-1] = 0 if seed % 3 == 0 else lengths[-1]
+    check(lengths, 4, "f16" if seed % 2 == 0 else "bf16", 400 + seed, max_seqlen=199)
+
+
+def test_all_images_empty():
+    q, k, v = _qkv(4, 2, "f16", 1)
+    got, raw = hp.gpu_attn(q[:0], k[:0], v[:0], hp.cu_from_lengths([0, 0, 0]), 197, 0.125, extra_rows=4)
+    assert np.all(got == 77.0)
+
+
+def test_headline_config_full_parity():
+    """DeiT-B shape, B=32, 80 % pruned, with the launch arguments the benchmark uses
+    (max_seqlen = N, no host knowledge of the lengths)."""
+    w = wl.deit_b_pruned(0.2)
+    q, k, v = w.qkv()
+    cu = hp.cu_from_lengths(w.lengths)
+    want = oracle.attn(wl.to_words(q), wl.to_words(k), wl.to_words(v), cu, w.scale, "f16", threads=8)
+    got, _ = hp.gpu_attn(q, k, v, cu, w.N, w.scale)
+    err = np.abs(got - want)
+    assert err.max() <= TOL
+    assert err.mean() < 2e-4                                  # paper's kernel rows: mean 1.6e-5..3e-5 vs fp16 SDPA
+
+
+@pytest.mark.parametrize("p", wl.SWEEP_KEEP_PROBS)
+def test_sweep_bf16_fp32_out(p):
+    w = wl.deit_b_pruned(p, 32, "bf16", 1002)
+    q, k, v = w.qkv()
+    cu = hp.cu_from_lengths(w.lengths)
+    want = oracle.attn(wl.to_words(q), wl.to_words(k), wl.to_words(v), cu, w.scale, "bf16", threads=8)
+    got, _ = hp.gpu_attn(q, k, v, cu, w.N, w.scale, out_dtype=torch.float32)
+    assert np.max(np.abs(got - want)) <= TOL
+    got, _ = hp.gpu_attn(q, k, v, cu, w.N, w.scale)           # bf16 out: output rounding added
+    assert np.all(np.abs(got - want) <= TOL + np.abs(want) * 2.0 ** -8)
+
+
+@pytest.mark.parametrize("B", [1, 2, 4, 32])
+def test_serving_384(B):
+    w = wl.serving_384(B)
+    q, k, v = w.qkv()
+    cu = hp.cu_from_lengths(w.lengths)
+    want = oracle.attn(wl.to_words(q), wl.to_words(k), wl.to_words(v), cu, w.scale, "f16", threads=8)
+    got, _ = hp.gpu_attn(q, k, v, cu, w.N, w.scale)
+    assert np.max(np.abs(got - want)) <= TOL
+
+
+def test_pipeline_layer1_sampled_rows():
+    """B=64, every token kept (T = 12,608): the oracle checks sampled rows one by one."""
+    w = wl.pipeline()[0]
+    q, k, v = w.qkv()
+    cu = hp.cu_from_lengths(w.lengths)
+    got, _ = hp.gpu_attn(q, k, v, cu, w.N, w.scale)
+    qw, kw, vw = wl.to_words(q), wl.to_words(k), wl.to_words(v)
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        i, h = int(rng.integers(w.B)), int(rng.integers(w.H))
+        r = int(rng.integers(cu[i + 1] - cu[i]))
+        _, o = oracle.attn_row(qw, kw, vw, cu, i, h, r, w.scale, "f16")
+        assert np.max(np.abs(got[cu[i] + r, h] - o)) <= TOL
+    assert np.all(np.isfinite(got))
+
+
+@pytest.mark.parametrize("scale", [0.0, -0.125, 1.0, 0.02])
+def test_scales(scale):
+    check([5, 70, 33], 2, "f16", 500, scale=scale, tol=TOL if abs(scale) < 1 else 4e-3)
+
+
+def test_single_token_sequences_return_v_bits():
+    lengths = [1] * 9
+    q, k, v = _qkv(9, 3, "f16", 600)
+    got, raw = hp.gpu_attn(q, k, v, hp.cu_from_lengths(lengths), 1, 0.125)
+    assert torch.equal(raw.view(torch.int16), v.view(torch.int16))
+
+
+def test_identical_v_rows_are_returned_within_one_ulp():
+    n, H = 50, 2
+    q, k, _ = _qkv(n, H, "f16", 601)
+    v1 = torch.randn(1, H, 64, generator=torch.Generator().manual_seed(3)).to(torch.float16)
+    v = v1.repeat(n, 1, 1).contiguous()
+    got, raw = hp.gpu_attn(q, k, v, hp.cu_from_lengths([n]), n, 0.125)
+    ulp = np.maximum(np.abs(v1.to(torch.float64).numpy()), 2.0 ** -14) * 2.0 ** -10
+    assert np.all(np.abs(got - v1.to(torch.float64).numpy()) <= ulp)
+
+
+def test_ragged_isolation_bit_exact():
+    """Replacing every token of image 1 must leave the other images' output bits unchanged: keys of
+    a neighbouring image never leak into a tile tail."""
+    lengths = [40, 70, 23, 197]
+    cu = hp.cu_from_lengths(lengths)
+    q, k, v = _qkv(int(cu[-1]), 3, "f16", 602)
+    q2, k2, v2 = _qkv(int(cu[-1]), 3, "f16", 603)
+    for a, b in ((q, q2), (k, k2), (v, v2)):
+        b[:40] = a[:40]
+        b[110:] = a[110:]
+    _, r1 = hp.gpu_attn(q, k, v, cu, 197, 0.125)
+    _, r2 = hp.gpu_attn(q2, k2, v2, cu, 197, 0.125)
+    a, b = r1.view(torch.int16), r2.view(torch.int16)
+    assert torch.equal(a[:40], b[:40]) and torch.equal(a[110:], b[110:])
+    assert not torch.equal(a[40:110], b[40:110])
+
+
+def test_run_to_run_determinism():
+    w = wl.deit_b_pruned(0.4, B=8)
+    q, k, v = w.qkv()
+    cu = hp.cu_from_lengths(w.lengths)
+    _, r1 = hp.gpu_attn(q, k, v, cu, w.N, w.scale)
+    for _ in range(3):
+        _, r2 = hp.gpu_attn(q, k, v, cu, w.N, w.scale)
+        assert torch.equal(r1.view(torch.int16), r2.view(torch.int16))
+
+
+def test_max_seqlen_only_bounds_the_grid():
+    """Any bound >= max n gives the same bits."""
+    lengths = [30, 64, 10]
+    cu = hp.cu_from_lengths(lengths)
+    q, k, v = _qkv(int(cu[-1]), 2, "f16", 604)
+    _, a = hp.gpu_attn(q, k, v, cu, 64, 0.125)
+    _, b = hp.gpu_attn(q, k, v, cu, 1000, 0.125)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_permutation_equivariance_within_tolerance():
+    n = 90
+    cu = hp.cu_from_lengths([n])
+    q, k, v = _qkv(n, 2, "f16", 605)
+    perm = torch.randperm(n, generator=torch.Generator().manual_seed(2))
+    a, _ = hp.gpu_attn(q, k, v, cu, n, 0.125)
+    b, _ = hp.gpu_attn(q[perm].contiguous(), k[perm].contiguous(), v[perm].contiguous(), cu, n, 0.125)
+    assert np.max(np.abs(a[perm.numpy()] - b)) <= TOL
