@@ -1,0 +1,284 @@
+"""Benchmark of the pack -> ragged attention -> unpack hot path on ONE MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--report PATH]
+
+A "step" is one pass of the whole path over one synthetic batch: ragged_pack (keep mask ->
+cu_seqlens, gather indices, packed rows), ragged_attn on seeded Q/K/V of the packed length using
+the cu_seqlens pack just wrote, ragged_unpack of the attention output with pack's gather indices.
+Inputs are resident in HBM before the timed region.  The default workload is the headline one:
+DeiT-Base attention geometry (N=197, H=12, D=64), B=32, 80 % pruned (keep probability 0.2), fp16.
+
+The single JSON line printed at the end carries, beside the whole-path throughput, the roofline of
+the dominant kernel (timed live with HIP events over graph replays of that kernel alone), the
+per-stage kernel times, the launch floor, and the CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MFMA_F16_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA, published
+REPLICAS = 20                    # copies of one kernel inside a graph when timing that kernel alone
+
+
+def make_workload(name: str):
+    from paper_2604_15408_amd import workloads as wl
+    if name == "headline":
+        return wl.deit_b_pruned(0.2, 32, "f16", 1001)
+    if name == "tiny":
+        return wl.tiny()
+    if name.startswith("keep"):                       # e.g. keep0.6 : bf16 sweep point
+        p = float(name[4:])
+        k = wl.SWEEP_KEEP_PROBS.index(p)
+        return wl.sweep()[k]
+    if name.startswith("serving"):                    # e.g. serving4
+        return wl.serving_384(int(name[7:]))
+    if name.startswith("layer"):                      # e.g. layer1 : pipeline layer (B=64)
+        return wl.pipeline()[int(name[5:]) - 1]
+    raise SystemExit(f"unknown workload {name!r}")
+
+
+class Path:
+    """Device buffers of one workload plus the three stage calls."""
+
+    def __init__(self, w, fill_mode: int = 0):
+        import torch
+        from paper_2604_15408_amd import binding
+        self.torch, self.b, self.w, self.fill_mode = torch, binding, w, fill_mode
+        dev = "cuda:0"
+        B, N, C, H, D = w.B, w.N, w.C, w.H, w.D
+        self.T = w.T
+        rows = max(self.T, 1)
+        self.x = w.features().to(dev)
+        self.keep = w.keep.to(dev)
+        self.packed = torch.zeros(B * N, C, dtype=self.x.dtype, device=dev)
+        self.cu = torch.zeros(B + 1, dtype=torch.int32, device=dev)
+        self.gidx = torch.zeros(B * N, dtype=torch.int32, device=dev)
+        q, k, v = w.qkv(rows)
+        self.q, self.k, self.v = q.to(dev), k.to(dev), v.to(dev)
+        self.o = torch.zeros(rows, H, D, dtype=self.q.dtype, device=dev)
+        self.out = torch.zeros(B, N, C, dtype=self.x.dtype, device=dev)
+        torch.cuda.synchronize()
+
+    def pack(self):
+        self.b.ragged_pack(self.x, self.keep, self.packed, self.cu, self.gidx)
+
+    def attn(self):
+        # max_seqlen = N: nothing about the lengths is known on the host (no sync after pack)
+        self.b.ragged_attn(self.q, self.k, self.v, self.o, self.cu, self.w.N, self.w.scale)
+
+    def unpack(self):
+        self.b.ragged_unpack(self.o.view(-1, self.w.C), self.keep, self.cu, self.gidx, self.out,
+                             self.fill_mode)
+
+    def step(self):
+        self.pack()
+        self.attn()
+        self.unpack()
+
+    # algorithmic bytes / flops of one launch of each stage (what the method itself must move)
+    def algorithmic(self):
+        w, T = self.w, self.T
+        row = w.C * 2
+        sq = sum(n * n for n in w.lengths)
+        unpack_bytes = 2 * T * row + 4 * T if self.fill_mode == 0 else T * row + w.B * w.N * row + w.B * w.N
+        return {
+            "pack": {"bytes": w.B * w.N + 2 * T * row + 4 * (w.B + 1) + 4 * T},
+            "attn": {"bytes": 4 * T * row, "flops": 4 * w.D * w.H * sq},
+            "unpack": {"bytes": unpack_bytes},
+        }
+
+
+def capture(torch, fn, reps: int = 1):
+    """Record `reps` calls of fn into one HIP graph (side stream, torch's capture plumbing)."""
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        fn()                                          # warm the code path outside capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            for _ in range(reps):
+                fn()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    return g
+
+
+def event_time_us(torch, launch, iters: int, warmup: int = 5):
+    """Median / mean GPU time of launch() in microseconds, HIP events on the launching stream."""
+    for _ in range(warmup):
+        launch()
+    torch.cuda.synchronize()
+    samples = []
+    for _ in range(iters):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        launch()
+        e1.record()
+        e1.synchronize()
+        samples.append(e0.elapsed_time(e1) * 1e3)
+    return statistics.median(samples), statistics.fmean(samples)
+
+
+def wall_steps(torch, fn, steps: int):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(w, fill_mode: int):
+    """The CPU oracle on the same workload, all host cores available to this process."""
+    import torch
+    import oracle
+    from paper_2604_15408_amd import workloads as wl
+    tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
+    cores = min(len(os.sched_getaffinity(0)), oracle.max_threads())
+    x = wl.to_words(w.features())
+    keep = w.keep.numpy()
+    q, k, v = (wl.to_words(t) for t in w.qkv())
+    times = []
+    for _ in range(3):
+        t0 = time.perf_counter()
+        packed, cu, gidx = oracle.pack(x, keep)
+        o = oracle.attn(q, k, v, cu, w.scale, w.dtype, threads=cores)
+        o16 = wl.to_words(torch.from_numpy(o).to(tdt)).reshape(-1, w.C)
+        oracle.unpack(o16, keep, cu, w.C, fill_mode)
+        times.append(time.perf_counter() - t0)
+    t = statistics.median(times)
+    return {"value": w.T / t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "ms_per_step": t * 1e3,
+            "sample": f"whole {w.name} batch (T={w.T}), pack+attn+unpack, median of 3 runs"}
+
+
+def run(args):
+    import torch
+    from paper_2604_15408_amd import binding
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (there is no CPU fallback of the product path)")
+    binding.load()
+    w = make_workload(args.workload)
+    p = Path(w, args.fill_mode)
+    alg = p.algorithmic()
+
+    # ---- whole path: one graph launch per step (the designed steady state) and eager launches
+    g_step = capture(torch, p.step)
+    for _ in range(args.warmup):
+        g_step.replay()
+        p.step()
+    t_graph = wall_steps(torch, g_step.replay, args.steps)
+    t_eager = wall_steps(torch, p.step, args.steps)
+    mode = "hipgraph" if t_graph <= t_eager else "eager"
+    t_step = min(t_graph, t_eager)
+
+    # ---- each kernel alone: REPLICAS back-to-back copies in one graph, HIP events around a replay
+    stage_us, stage_mean_us = {}, {}
+    for name, fn in (("pack", p.pack), ("attn", p.attn), ("unpack", p.unpack)):
+        g = capture(torch, fn, REPLICAS)
+        med, mean = event_time_us(torch, g.replay, iters=max(20, args.steps // 10))
+        stage_us[name], stage_mean_us[name] = med / REPLICAS, mean / REPLICAS
+    g_pipe = capture(torch, p.step, REPLICAS)
+    pipe_us = event_time_us(torch, g_pipe.replay, iters=max(20, args.steps // 10))[0] / REPLICAS
+
+    # ---- launch floor: an empty kernel, same grid size as the attention launch
+    attn_grid = w.B * w.H * ((w.N + 63) // 64)
+    noop = lambda: binding.ragged_noop(attn_grid)
+    g_noop = capture(torch, noop, REPLICAS)
+    g_noop1 = capture(torch, noop, 1)
+    floor = {
+        "noop_kernel_in_graph_us": event_time_us(torch, g_noop.replay, 20)[0] / REPLICAS,
+        "noop_eager_wall_us": wall_steps(torch, lambda: (noop(), torch.cuda.synchronize()), 200) * 1e6,
+        "noop_graph_launch_wall_us": wall_steps(torch, lambda: (g_noop1.replay(), torch.cuda.synchronize()), 200) * 1e6,
+        "noop_eager_enqueue_us": wall_steps(torch, noop, 1000) * 1e6,
+        "attn_eager_wall_us": wall_steps(torch, lambda: (p.attn(), torch.cuda.synchronize()), 200) * 1e6,
+        "attn_eager_enqueue_us": wall_steps(torch, p.attn, 1000) * 1e6,
+    }
+
+    # HBM traffic per launch comes from rocprofv3 --pmc passes made offline over this same command
+    # (a counter run cannot share a process with timing); null if this workload was not profiled.
+    traffic = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            traffic = json.load(f).get(w.name, {})
+    except OSError:
+        pass
+    dominant = max(stage_us, key=stage_us.get)
+    dom_us = stage_mean_us[dominant]
+    achieved = alg[dominant]["bytes"] / (dom_us * 1e-6) / 1e9
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": traffic.get(dominant, {}).get("hbm_bytes"),
+                "avg_launch_us": dom_us, "algorithmic_bytes": alg[dominant]["bytes"]}
+    attn_tflops = alg["attn"]["flops"] / (stage_us["attn"] * 1e-6) / 1e12
+
+    result = {
+        "metric": "packed tokens/s through pack+ragged_attn+unpack (DeiT-B shape, 80% pruned, BS=32); ragged_attn us/call in extras",
+        "value": w.T / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": t_step * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "N": w.N, "H": w.H, "D": w.D, "T": w.T,
+                   "max_len": max(w.lengths), "lengths": w.note, "launch": mode,
+                   "unpack_fill_mode": args.fill_mode},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline(w, args.fill_mode),
+        "extras": {
+            "ragged_attn_us_per_call": stage_us["attn"],
+            "ragged_attn_tokens_per_s": w.T / (stage_us["attn"] * 1e-6),
+            "kernel_us": stage_us, "pipeline_kernels_us": pipe_us,
+            "step_wall_us": {"hipgraph": t_graph * 1e6, "eager": t_eager * 1e6},
+            "attn_mfma_tflops": attn_tflops, "attn_mfma_frac": attn_tflops / MFMA_F16_PEAK_TFLOPS,
+            "stage_gbs": {k: alg[k]["bytes"] / (stage_us[k] * 1e-6) / 1e9 for k in stage_us},
+            "floor": floor,
+            "paper_context": "paper's Triton kernel on RTX 4000 Ada: 24 us attention latency at BS=32, 40 tok/img (uniform lengths)",
+        },
+    }
+    return result
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="headline")
+    ap.add_argument("--fill-mode", type=int, default=0, choices=(0, 1))
+    ap.add_argument("--report", default=None, help="also write the JSON to this path")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 64 MiB elementwise copy kernel (known traffic) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (images are independent, so the path "
+              "shards by image with no exchange step; see DESIGN.md); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    result = run(args)
+    if args.calibrate_copy:
+        import torch
+        src = torch.arange(16 << 20, dtype=torch.int32, device="cuda:0")      # 64 MiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1, out=dst)                                        # reads 64 MiB, writes 64 MiB
+        torch.cuda.synchronize()
+    line = json.dumps(result)
+    if args.report:
+        os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
+        with open(args.report, "w") as f:
+            f.write(line + "\n")
+    print(line)
+
+
+if __name__ == "__main__":
+    main()

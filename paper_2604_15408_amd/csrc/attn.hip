@@ -103,28 +103,26 @@ __device__ __forceinline__ void store16(float* dst, const float (&v)[16]) {
         reinterpret_cast<float4*>(dst)[e] = make_float4(v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]);
 }
 
-// Work-group index -> logical work item.  The hardware deals consecutive work-groups round-robin
-// to the 8 XCDs (each with its own L2).  Giving XCD x the contiguous slice [x*per, (x+1)*per) of
-// logical items keeps the q-tiles of one (image, head) -- which re-read the same K/V -- and the
-// heads of one image on one L2.
-__device__ __forceinline__ int logical_item(int bid, int per_xcd) {
-    return (bid % kXcds) * per_xcd + bid / kXcds;
-}
-
+// Work-group index -> (q-tile, image-head pair).  bid = m_tile * pairs8 + pair, where pairs8 is
+// B*H rounded up to a multiple of 8:
+//   * the hardware deals consecutive work-groups round-robin to the 8 XCDs (each with its own L2),
+//     so every q-tile of a pair lands on XCD pair%8 and re-reads that pair's K/V from one L2;
+//   * q-tile 0 of every pair is dispatched first.  The grid is sized by max_seqlen, an upper bound;
+//     with ragged lengths most of the surplus tiles are the high ones, which now sit at the END of
+//     the dispatch order and retire while the real tiles are already running.
 template <typename In, typename OutT>
 __global__ __launch_bounds__(kBlockThreads)
 void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                  const uint16_t* __restrict__ v, OutT* __restrict__ o,
-                 const int32_t* __restrict__ cu_seqlens, int H, int q_tiles, int items,
-                 int per_xcd, float scale_log2e) {
+                 const int32_t* __restrict__ cu_seqlens, int H, int pairs, int pairs8,
+                 float scale_log2e) {
     typedef typename In::vec8 vec8;
     __shared__ __attribute__((aligned(16))) uint16_t k_lds[kBN * kLdsStride];
     __shared__ __attribute__((aligned(16))) uint16_t vt_lds[kHeadDim * kLdsStride];
 
-    const int item = logical_item(blockIdx.x, per_xcd);
-    if (item >= items) return;
-    const int m_tile = item % q_tiles;
-    const int pair = item / q_tiles;
+    const int m_tile = blockIdx.x / pairs8;
+    const int pair = blockIdx.x - m_tile * pairs8;
+    if (pair >= pairs) return;
     const int h = pair % H;
     const int img = pair / H;
     const int s = cu_seqlens[img];
@@ -286,12 +284,12 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
                         const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
                         hipStream_t stream) {
     const int q_tiles = (max_seqlen + kBM - 1) / kBM;
-    const int items = B * H * q_tiles;
-    const int per_xcd = (items + kXcds - 1) / kXcds;
-    hipLaunchKernelGGL((attn_kernel<In, OutT>), dim3(per_xcd * kXcds), dim3(kBlockThreads), 0, stream,
+    const int pairs = B * H;
+    const int pairs8 = (pairs + kXcds - 1) / kXcds * kXcds;
+    hipLaunchKernelGGL((attn_kernel<In, OutT>), dim3(q_tiles * pairs8), dim3(kBlockThreads), 0, stream,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                        static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, H,
-                       q_tiles, items, per_xcd, scale * kLog2e);
+                       pairs, pairs8, scale * kLog2e);
     return hipGetLastError();
 }
 
