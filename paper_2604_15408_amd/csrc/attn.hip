@@ -103,6 +103,101 @@ __device__ __forceinline__ void store16(float* dst, const float (&v)[16]) {
         reinterpret_cast<float4*>(dst)[e] = make_float4(v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]);
 }
 
+// Reductions over the four lanes that share a query (l, l^16, l^32, l^48) with the gfx950 lane-swap
+// instructions (pure VALU, no LDS round trip).  permlane32_swap(a, b) returns {a.lo|b.lo, a.hi|b.hi}
+// (32-lane halves); permlane16_swap(a, b) returns {a.row0,b.row0,a.row2,b.row2} and
+// {a.row1,b.row1,a.row3,b.row3} (16-lane rows).  With b a copy of a, combining the two results
+// reduces across the halves, then across the rows.  The copy is made through an opaque move so the
+// two operands can never be folded into one register (the instruction swaps its operands in place).
+__device__ __forceinline__ unsigned opaque_copy(unsigned x) {
+    unsigned y;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(y) : "v"(x));
+    return y;
+}
+__device__ __forceinline__ float as_f32(unsigned u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
+__device__ __forceinline__ float quad_max(float x) {
+    const auto a = __builtin_amdgcn_permlane32_swap(as_u32(x), opaque_copy(as_u32(x)), false, false);
+    const unsigned a0 = a[0], a1 = a[1];
+    x = fmaxf(as_f32(a0), as_f32(a1));
+    const auto b = __builtin_amdgcn_permlane16_swap(as_u32(x), opaque_copy(as_u32(x)), false, false);
+    const unsigned b0 = b[0], b1 = b[1];
+    return fmaxf(as_f32(b0), as_f32(b1));
+}
+__device__ __forceinline__ float quad_sum(float x) {
+    const auto a = __builtin_amdgcn_permlane32_swap(as_u32(x), opaque_copy(as_u32(x)), false, false);
+    const unsigned a0 = a[0], a1 = a[1];
+    x = as_f32(a0) + as_f32(a1);
+    const auto b = __builtin_amdgcn_permlane16_swap(as_u32(x), opaque_copy(as_u32(x)), false, false);
+    const unsigned b0 = b[0], b1 = b[1];
+    return as_f32(b0) + as_f32(b1);
+}
+
+// One K/V tile (<= 64 keys, already in LDS) against this wavefront's 16 queries: S^T = K Q^T,
+// online-softmax update, O^T += V^T P^T.  FULL: all 64 keys are valid (no tail masking).
+// scale_log2e >= 0 here (a negative softmax scale is folded into the sign of Q by the caller), so
+// the row maximum can be taken on the raw scores and the scale fused into the exponent's FMA.
+template <typename In, bool FULL>
+__device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
+                                            const uint16_t* __restrict__ vt_tile,
+                                            const typename In::vec8 (&q_frag)[2], int rem, int col, int g,
+                                            float scale_log2e, float& m_run, float& l_run,
+                                            f32x4 (&o_acc)[4]) {
+    typedef typename In::vec8 vec8;
+    // -------- S^T = K Q^T : four 16-key tiles, two k-steps of 32 head-dim elements
+    f32x4 st[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+        st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (FULL || 16 * kt < rem) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const uint4 a = *reinterpret_cast<const uint4*>(
+                    &k_tile[(16 * kt + col) * kLdsStride + 16 * g + 8 * ks]);
+                st[kt] = In::mfma(as_vec8<vec8>(a), q_frag[ks], st[kt]);
+            }
+        }
+    }
+    // -------- online softmax (this lane: one query, keys 16*kt + 4*g + r of the tile)
+    float t_max = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            t_max = fmaxf(t_max, (FULL || 16 * kt + 4 * g + r < rem) ? st[kt][r] : -INFINITY);
+    t_max = quad_max(t_max);
+    const float m_new = fmaxf(m_run, t_max * scale_log2e);      // finite: the tile has a valid key
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float t_sum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], scale_log2e, -m_new));
+            if (!FULL) p = (16 * kt + 4 * g + r < rem) ? p : 0.f;
+            st[kt][r] = p;
+            t_sum += p;
+        }
+    l_run = l_run * alpha + t_sum;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) o_acc[dt] *= alpha;
+    // -------- O^T += V^T P^T : two 32-key blocks x four 16-row head-dim tiles
+#pragma unroll
+    for (int bb = 0; bb < 2; ++bb) {
+        if (FULL || 32 * bb < rem) {
+            uint4 vt[4];
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                vt[dt] = *reinterpret_cast<const uint4*>(
+                    &vt_tile[(16 * dt + col) * kLdsStride + 32 * bb + 8 * g]);
+            const float p[8] = {st[2 * bb][0], st[2 * bb][1], st[2 * bb][2], st[2 * bb][3],
+                                st[2 * bb + 1][0], st[2 * bb + 1][1], st[2 * bb + 1][2], st[2 * bb + 1][3]};
+            pv_block(In{}, vt, p, o_acc);
+        }
+    }
+}
+
 // Work-group index -> (q-tile, image-head pair).  bid = m_tile * pairs8 + pair, where pairs8 is
 // B*H rounded up to a multiple of 8:
 //   * the hardware deals consecutive work-groups round-robin to the 8 XCDs (each with its own L2),
@@ -110,15 +205,19 @@ __device__ __forceinline__ void store16(float* dst, const float (&v)[16]) {
 //   * q-tile 0 of every pair is dispatched first.  The grid is sized by max_seqlen, an upper bound;
 //     with ragged lengths most of the surplus tiles are the high ones, which now sit at the END of
 //     the dispatch order and retire while the real tiles are already running.
+//
+// K/V tiles are double-buffered in LDS and the next tile's global loads are issued before the
+// current tile is computed, so one barrier per tile suffices and the fabric latency of tile t+1 is
+// hidden behind the arithmetic of tile t.
 template <typename In, typename OutT>
-__global__ __launch_bounds__(kBlockThreads)
+__global__ __launch_bounds__(kBlockThreads, 4)
 void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                  const uint16_t* __restrict__ v, OutT* __restrict__ o,
                  const int32_t* __restrict__ cu_seqlens, int H, int pairs, int pairs8,
-                 float scale_log2e) {
+                 float scale_log2e, int negate_q) {
     typedef typename In::vec8 vec8;
-    __shared__ __attribute__((aligned(16))) uint16_t k_lds[kBN * kLdsStride];
-    __shared__ __attribute__((aligned(16))) uint16_t vt_lds[kHeadDim * kLdsStride];
+    __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kBN * kLdsStride];
+    __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][kHeadDim * kLdsStride];
 
     const int m_tile = blockIdx.x / pairs8;
     const int pair = blockIdx.x - m_tile * pairs8;
@@ -137,50 +236,30 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int g = lane >> 4;                                   // lane group
     const int64_t tok = (int64_t)H * kHeadDim;                 // elements between tokens
     const int64_t head_off = (int64_t)h * kHeadDim;
-
-    // ---- Q: this lane's query row, head-dim elements 16g .. 16g+15 (zeros past the sequence end)
-    const int q_row = m0 + wave * 16 + col;
-    uint4 q_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
-    if (q_row < n) {
-        const uint4* src = reinterpret_cast<const uint4*>(q + (s + q_row) * tok + head_off + 16 * g);
-        q_raw[0] = src[0];
-        q_raw[1] = src[1];
-    }
-    const vec8 q_frag[2] = {as_vec8<vec8>(q_raw[0]), as_vec8<vec8>(q_raw[1])};
+    const bool wave_active = m0 + wave * 16 < n;               // wavefront has at least one real query
 
     // ---- tile-fill roles: wavefronts 0-1 copy K (4 x 16 B each), wavefronts 2-3 transpose V
     const int fill = tid & 127;
     const int fill_dc = fill & 7;                              // which 8-element slice of the head dim
     const int fill_kg = fill >> 3;                             // K: key = fill_kg + 16*a ; V: keys 4*fill_kg + a
     const bool fills_k = tid < 128;
+    const uint16_t* fill_src = (fills_k ? k : v) + s * tok + head_off + 8 * fill_dc;
 
-    float m_run = -INFINITY;                                   // running max (log2 domain)
-    float l_run = 0.f;                                         // running sum, this lane's keys only
-    f32x4 o_acc[4];
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) o_acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    for (int j0 = 0; j0 < n; j0 += kBN) {
-        const int rem = n - j0;                                // valid keys in this tile (>= 1)
-        // -------- global -> registers
-        uint4 raw[4];
+    uint4 raw[4];
+    auto prefetch = [&](int j0) {
+        const int rem = n - j0;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             const int key = fills_k ? fill_kg + 16 * a : 4 * fill_kg + a;
-            raw[a] = make_uint4(0, 0, 0, 0);
-            if (key < rem) {
-                const uint16_t* base = fills_k ? k : v;
-                raw[a] = *reinterpret_cast<const uint4*>(base + (s + j0 + key) * tok + head_off + 8 * fill_dc);
-            }
+            raw[a] = make_uint4(0, 0, 0, 0);                   // keys past n are zero in LDS
+            if (key < rem) raw[a] = *reinterpret_cast<const uint4*>(fill_src + (j0 + key) * tok);
         }
-        if (j0 > 0) __syncthreads();                           // previous tile fully consumed
-        // -------- registers -> LDS
+    };
+    auto stage = [&](int buf) {
         if (fills_k) {
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int key = fill_kg + 16 * a;
-                *reinterpret_cast<uint4*>(&k_lds[key * kLdsStride + 8 * fill_dc]) = raw[a];
-            }
+            for (int a = 0; a < 4; ++a)
+                *reinterpret_cast<uint4*>(&k_lds[buf][(fill_kg + 16 * a) * kLdsStride + 8 * fill_dc]) = raw[a];
         } else {
             // keys 4*fill_kg .. +3 occupy 4 consecutive kappa slots
             const int key0 = 4 * fill_kg;
@@ -201,81 +280,63 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     packed4.x = (w[0][e >> 1] & 0xffffu) | (w[1][e >> 1] << 16);
                     packed4.y = (w[2][e >> 1] & 0xffffu) | (w[3][e >> 1] << 16);
                 }
-                *reinterpret_cast<uint2*>(&vt_lds[rho * kLdsStride + kappa]) = packed4;
+                *reinterpret_cast<uint2*>(&vt_lds[buf][rho * kLdsStride + kappa]) = packed4;
             }
         }
-        __syncthreads();
+    };
 
-        // -------- S^T = K Q^T : four 16-key tiles, two k-steps of 32 head-dim elements
-        f32x4 st[4];
+    prefetch(0);
+
+    // ---- Q: this lane's query row, head-dim elements 16g .. 16g+15 (zeros past the sequence end)
+    const int q_row = m0 + wave * 16 + col;
+    uint4 q_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+    if (q_row < n) {
+        const uint4* src = reinterpret_cast<const uint4*>(q + (s + q_row) * tok + head_off + 16 * g);
+        q_raw[0] = src[0];
+        q_raw[1] = src[1];
+    }
+    if (negate_q) {                                            // softmax(-|c| q.k) == softmax(|c| (-q).k)
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
-            st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (16 * kt < rem) {
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const uint4 a = *reinterpret_cast<const uint4*>(
-                        &k_lds[(16 * kt + col) * kLdsStride + 16 * g + 8 * ks]);
-                    st[kt] = In::mfma(as_vec8<vec8>(a), q_frag[ks], st[kt]);
-                }
-            }
+        for (int e = 0; e < 2; ++e) {
+            q_raw[e].x ^= 0x80008000u; q_raw[e].y ^= 0x80008000u;
+            q_raw[e].z ^= 0x80008000u; q_raw[e].w ^= 0x80008000u;
         }
+    }
+    const vec8 q_frag[2] = {as_vec8<vec8>(q_raw[0]), as_vec8<vec8>(q_raw[1])};
 
-        // -------- online softmax (this lane: one query, keys j0 + 16*kt + 4*g + r)
-        float t_max = -INFINITY;
+    float m_run = -INFINITY;                                   // running max (log2 domain)
+    float l_run = 0.f;                                         // running sum, this lane's keys only
+    f32x4 o_acc[4];
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float sc = (16 * kt + 4 * g + r < rem) ? st[kt][r] * scale_log2e : -INFINITY;
-                st[kt][r] = sc;
-                t_max = fmaxf(t_max, sc);
-            }
-        t_max = fmaxf(t_max, __shfl_xor(t_max, 16, kWaveSize));
-        t_max = fmaxf(t_max, __shfl_xor(t_max, 32, kWaveSize));
-        const float m_new = fmaxf(m_run, t_max);               // finite: the tile has a valid key
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        float t_sum = 0.f;
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float p = __builtin_amdgcn_exp2f(st[kt][r] - m_new);
-                st[kt][r] = p;
-                t_sum += p;
-            }
-        l_run = l_run * alpha + t_sum;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) o_acc[dt] *= alpha;
+    for (int dt = 0; dt < 4; ++dt) o_acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        // -------- O^T += V^T P^T : two 32-key blocks x four 16-row head-dim tiles
-#pragma unroll
-        for (int bb = 0; bb < 2; ++bb) {
-            if (32 * bb < rem) {
-                uint4 vt[4];
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-                    vt[dt] = *reinterpret_cast<const uint4*>(
-                        &vt_lds[(16 * dt + col) * kLdsStride + 32 * bb + 8 * g]);
-                const float p[8] = {st[2 * bb][0], st[2 * bb][1], st[2 * bb][2], st[2 * bb][3],
-                                    st[2 * bb + 1][0], st[2 * bb + 1][1], st[2 * bb + 1][2], st[2 * bb + 1][3]};
-                pv_block(In{}, vt, p, o_acc);
-            }
+    const int tiles = (n + kBN - 1) / kBN;
+    for (int t = 0; t < tiles; ++t) {
+        const int buf = t & 1;
+        stage(buf);                         // buffer `buf` was last read two tiles ago: see barrier below
+        __syncthreads();                    // tile t visible; every wavefront is past tile t-1's reads
+        if (t + 1 < tiles) prefetch((t + 1) * kBN);
+        if (wave_active) {
+            const int rem = n - t * kBN;
+            if (rem >= kBN)
+                tile_update<In, true>(k_lds[buf], vt_lds[buf], q_frag, rem, col, g, scale_log2e, m_run, l_run, o_acc);
+            else
+                tile_update<In, false>(k_lds[buf], vt_lds[buf], q_frag, rem, col, g, scale_log2e, m_run, l_run, o_acc);
         }
     }
 
     // ---- normalise and store: this lane owns d = 16g + 4r + dt of its query
-    float l_tot = l_run + __shfl_xor(l_run, 16, kWaveSize);
-    l_tot += __shfl_xor(l_tot, 32, kWaveSize);
-    if (q_row < n) {
-        const float inv = 1.0f / l_tot;
-        float out16[16];
+    if (wave_active) {
+        const float l_tot = quad_sum(l_run);
+        if (q_row < n) {
+            const float inv = 1.0f / l_tot;
+            float out16[16];
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+            for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) out16[4 * r + dt] = o_acc[dt][r] * inv;
-        store16(o + (s + q_row) * tok + head_off + 16 * g, out16);
+                for (int r = 0; r < 4; ++r) out16[4 * r + dt] = o_acc[dt][r] * inv;
+            store16(o + (s + q_row) * tok + head_off + 16 * g, out16);
+        }
     }
 }
 
@@ -289,7 +350,7 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
     hipLaunchKernelGGL((attn_kernel<In, OutT>), dim3(q_tiles * pairs8), dim3(kBlockThreads), 0, stream,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                        static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, H,
-                       pairs, pairs8, scale * kLog2e);
+                       pairs, pairs8, fabsf(scale) * kLog2e, scale < 0.f ? 1 : 0);
     return hipGetLastError();
 }
 
