@@ -39,10 +39,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kHeadDim = 64;
-constexpr int kBM = 64;                 // queries per work-group (16 per wavefront)
 constexpr int kBN = 64;                 // keys per K/V tile
 constexpr int kLdsStride = 72;          // halves per LDS row: 64 + 8 of padding (144 bytes)
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazyLog2 = 8.0f;       // probabilities stay below 2^8 between rescales
 
 struct F16 {
     typedef f16x8 vec8;
@@ -60,26 +60,35 @@ struct BF16 {
 template <typename V>
 __device__ __forceinline__ V as_vec8(uint4 raw) { return __builtin_bit_cast(V, raw); }
 
-// O^T += V^T P^T for one 32-key block: p[0..7] are this lane's probabilities (fp32).
-__device__ __forceinline__ void pv_block(F16, const uint4 (&vt)[4], const float (&p)[8], f32x4 (&o)[4]) {
-    f16x8 pb;
+// O^T += V^T P^T for one 32-key block: p[0..7] are this lane's probabilities (fp32).  The row sums
+// of P ride along on the matrix core: with an all-ones A operand every row of the result holds
+// sum_k P[k][query], already reduced over the four lane groups, and it is the sum of exactly the
+// rounded probabilities that multiply V.
+__device__ __forceinline__ void pv_block(F16, const uint4 (&vt)[4], const float (&p)[8], f32x4 (&o)[4],
+                                         f32x4& l) {
+    f16x8 pb, ones;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[e];
+    for (int e = 0; e < 8; ++e) { pb[e] = (_Float16)p[e]; ones[e] = (_Float16)1.0f; }
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) o[dt] = F16::mfma(as_vec8<f16x8>(vt[dt]), pb, o[dt]);
+    l = F16::mfma(ones, pb, l);
 }
-__device__ __forceinline__ void pv_block(BF16, const uint4 (&vt)[4], const float (&p)[8], f32x4 (&o)[4]) {
-    bf16x8 hi, lo;
+__device__ __forceinline__ void pv_block(BF16, const uint4 (&vt)[4], const float (&p)[8], f32x4 (&o)[4],
+                                         f32x4& l) {
+    bf16x8 hi, lo, ones;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         hi[e] = (__bf16)p[e];
         lo[e] = (__bf16)(p[e] - (float)hi[e]);
+        ones[e] = (__bf16)1.0f;
     }
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
         o[dt] = BF16::mfma(as_vec8<bf16x8>(vt[dt]), hi, o[dt]);
         o[dt] = BF16::mfma(as_vec8<bf16x8>(vt[dt]), lo, o[dt]);
     }
+    l = BF16::mfma(ones, hi, l);
+    l = BF16::mfma(ones, lo, l);
 }
 
 // Store 16 consecutive head-dim elements of one output row.
@@ -124,77 +133,74 @@ __device__ __forceinline__ float quad_max(float x) {
     const unsigned b0 = b[0], b1 = b[1];
     return fmaxf(as_f32(b0), as_f32(b1));
 }
-__device__ __forceinline__ float quad_sum(float x) {
-    const auto a = __builtin_amdgcn_permlane32_swap(as_u32(x), opaque_copy(as_u32(x)), false, false);
-    const unsigned a0 = a[0], a1 = a[1];
-    x = as_f32(a0) + as_f32(a1);
-    const auto b = __builtin_amdgcn_permlane16_swap(as_u32(x), opaque_copy(as_u32(x)), false, false);
-    const unsigned b0 = b[0], b1 = b[1];
-    return as_f32(b0) + as_f32(b1);
-}
-
-// One K/V tile (<= 64 keys, already in LDS) against this wavefront's 16 queries: S^T = K Q^T,
-// online-softmax update, O^T += V^T P^T.  FULL: all 64 keys are valid (no tail masking).
+// One K/V tile (already in LDS) against this wavefront's 16 queries: S^T = K Q^T, online-softmax
+// update, O^T += V^T P^T.  NT = 16-key subtiles present in the tile (1..4); MASK: the last subtile may
+// hold keys past the end of the sequence (index >= rem), which are masked out.
 // scale_log2e >= 0 here (a negative softmax scale is folded into the sign of Q by the caller), so
 // the row maximum can be taken on the raw scores and the scale fused into the exponent's FMA.
-template <typename In, bool FULL>
+template <typename In, int NT, bool MASK>
 __device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
                                             const uint16_t* __restrict__ vt_tile,
                                             const typename In::vec8 (&q_frag)[2], int rem, int col, int g,
-                                            float scale_log2e, float& m_run, float& l_run,
+                                            float scale_log2e, float& m_run, f32x4& l_acc,
                                             f32x4 (&o_acc)[4]) {
     typedef typename In::vec8 vec8;
-    // -------- S^T = K Q^T : four 16-key tiles, two k-steps of 32 head-dim elements
-    f32x4 st[4];
+    // -------- S^T = K Q^T : NT 16-key subtiles, two k-steps of 32 head-dim elements
+    f32x4 st[NT];
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
+    for (int kt = 0; kt < NT; ++kt) {
         st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (FULL || 16 * kt < rem) {
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const uint4 a = *reinterpret_cast<const uint4*>(
-                    &k_tile[(16 * kt + col) * kLdsStride + 16 * g + 8 * ks]);
-                st[kt] = In::mfma(as_vec8<vec8>(a), q_frag[ks], st[kt]);
-            }
+        for (int ks = 0; ks < 2; ++ks) {
+            const uint4 a = *reinterpret_cast<const uint4*>(
+                &k_tile[(16 * kt + col) * kLdsStride + 16 * g + 8 * ks]);
+            st[kt] = In::mfma(as_vec8<vec8>(a), q_frag[ks], st[kt]);
         }
     }
     // -------- online softmax (this lane: one query, keys 16*kt + 4*g + r of the tile)
+    const int last_valid = rem - 16 * (NT - 1) - 4 * g;        // r < last_valid is a real key (last subtile)
     float t_max = -INFINITY;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+    for (int kt = 0; kt < NT; ++kt)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            t_max = fmaxf(t_max, (FULL || 16 * kt + 4 * g + r < rem) ? st[kt][r] : -INFINITY);
-    t_max = quad_max(t_max);
-    const float m_new = fmaxf(m_run, t_max * scale_log2e);      // finite: the tile has a valid key
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    float t_sum = 0.f;
+            t_max = fmaxf(t_max, (!MASK || kt < NT - 1 || r < last_valid) ? st[kt][r] : -INFINITY);
+    t_max = quad_max(t_max) * scale_log2e;                      // finite: the tile has a valid key
+    // Lazy rescaling: the reference maximum m_run only moves when some query's tile maximum exceeds
+    // it by more than 2^kLazyLog2 (always on the first tile, where m_run = -inf).  Until then
+    // probabilities may reach 2^kLazyLog2 instead of 1 -- harmless in fp16/bf16/fp32 -- and the
+    // accumulators need no per-tile multiply.  The result is the same softmax: m_run cancels.
+    if (__builtin_amdgcn_ballot_w64(t_max > m_run + kLazyLog2) != 0) {   // wavefront-uniform
+        const float m_new = fmaxf(m_run, t_max);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_acc *= alpha;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+        for (int dt = 0; dt < 4; ++dt) o_acc[dt] *= alpha;
+    }
+#pragma unroll
+    for (int kt = 0; kt < NT; ++kt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], scale_log2e, -m_new));
-            if (!FULL) p = (16 * kt + 4 * g + r < rem) ? p : 0.f;
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][r], scale_log2e, -m_run));
+            if (MASK && kt == NT - 1) p = (r < last_valid) ? p : 0.f;
             st[kt][r] = p;
-            t_sum += p;
         }
-    l_run = l_run * alpha + t_sum;
+    // -------- O^T += V^T P^T : 32-key blocks x four 16-row head-dim tiles (odd NT: zero upper half)
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) o_acc[dt] *= alpha;
-    // -------- O^T += V^T P^T : two 32-key blocks x four 16-row head-dim tiles
+    for (int bb = 0; bb < (NT + 1) / 2; ++bb) {
+        uint4 vt[4];
 #pragma unroll
-    for (int bb = 0; bb < 2; ++bb) {
-        if (FULL || 32 * bb < rem) {
-            uint4 vt[4];
+        for (int dt = 0; dt < 4; ++dt)
+            vt[dt] = *reinterpret_cast<const uint4*>(
+                &vt_tile[(16 * dt + col) * kLdsStride + 32 * bb + 8 * g]);
+        float p[8];
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-                vt[dt] = *reinterpret_cast<const uint4*>(
-                    &vt_tile[(16 * dt + col) * kLdsStride + 32 * bb + 8 * g]);
-            const float p[8] = {st[2 * bb][0], st[2 * bb][1], st[2 * bb][2], st[2 * bb][3],
-                                st[2 * bb + 1][0], st[2 * bb + 1][1], st[2 * bb + 1][2], st[2 * bb + 1][3]};
-            pv_block(In{}, vt, p, o_acc);
+        for (int r = 0; r < 4; ++r) {
+            p[r] = st[2 * bb][r];
+            p[4 + r] = (2 * bb + 1 < NT) ? st[(2 * bb + 1 < NT) ? 2 * bb + 1 : 0][r] : 0.f;
         }
+        pv_block(In{}, vt, p, o_acc, l_acc);
     }
 }
 
@@ -206,16 +212,22 @@ __device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
 //     with ragged lengths most of the surplus tiles are the high ones, which now sit at the END of
 //     the dispatch order and retire while the real tiles are already running.
 //
-// K/V tiles are double-buffered in LDS and the next tile's global loads are issued before the
-// current tile is computed, so one barrier per tile suffices and the fabric latency of tile t+1 is
-// hidden behind the arithmetic of tile t.
-template <typename In, typename OutT>
-__global__ __launch_bounds__(kBlockThreads, 4)
+// A work-group has WAVES wavefronts of 16 queries each (q-tile = 16*WAVES rows).  K/V tiles of 64
+// keys are double-buffered in LDS and the next tile's global loads are issued before the current
+// tile is computed, so one barrier per tile suffices and the fabric latency of tile t+1 hides
+// behind the arithmetic of tile t.  The lower half of the threads copies K, the upper half
+// transposes V.
+template <typename In, typename OutT, int WAVES>
+__global__ __launch_bounds__(kWaveSize * WAVES, 4)
 void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                  const uint16_t* __restrict__ v, OutT* __restrict__ o,
                  const int32_t* __restrict__ cu_seqlens, int H, int pairs, int pairs8,
                  float scale_log2e, int negate_q) {
     typedef typename In::vec8 vec8;
+    constexpr int kBM = 16 * WAVES;                            // queries per work-group
+    constexpr int kHalf = 32 * WAVES;                          // threads per fill role
+    constexpr int kKLoads = 512 / kHalf;                       // 16-byte K units per K thread
+    constexpr int kKeyStep = kHalf / 8;                        // keys between a K thread's units
     __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kBN * kLdsStride];
     __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][kHeadDim * kLdsStride];
 
@@ -238,39 +250,57 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int64_t head_off = (int64_t)h * kHeadDim;
     const bool wave_active = m0 + wave * 16 < n;               // wavefront has at least one real query
 
-    // ---- tile-fill roles: wavefronts 0-1 copy K (4 x 16 B each), wavefronts 2-3 transpose V
-    const int fill = tid & 127;
-    const int fill_dc = fill & 7;                              // which 8-element slice of the head dim
-    const int fill_kg = fill >> 3;                             // K: key = fill_kg + 16*a ; V: keys 4*fill_kg + a
-    const bool fills_k = tid < 128;
-    const uint16_t* fill_src = (fills_k ? k : v) + s * tok + head_off + 8 * fill_dc;
+    // ---- tile-fill roles
+    const bool fills_k = tid < kHalf;
+    const int fill = fills_k ? tid : tid - kHalf;
+    // K thread: 16-byte units (key = fill/8 + kKeyStep*a, dims 8*(fill%8) ..)
+    // V thread, WAVES == 4: keys 4*(fill/8)  .. +3, dims 8*(fill%8)  .. +7  (4 x 16-byte loads)
+    //           WAVES == 8: keys 4*(fill/16) .. +3, dims 4*(fill%16) .. +3  (4 x  8-byte loads)
+    const int v_kg = (WAVES == 4) ? fill >> 3 : fill >> 4;
+    const int v_d0 = (WAVES == 4) ? 8 * (fill & 7) : 4 * (fill & 15);
+    const uint16_t* fill_src = fills_k ? k + (s + (fill >> 3)) * tok + head_off + 8 * (fill & 7)
+                                       : v + (s + 4 * v_kg) * tok + head_off + v_d0;
+    const int64_t fill_step = fills_k ? kKeyStep * tok : tok;  // elements between this thread's loads
+    const int fill_key0 = fills_k ? (fill >> 3) : 4 * v_kg;
+    const int fill_dkey = fills_k ? kKeyStep : 1;
+    // V thread's 4 keys occupy 4 consecutive kappa slots
+    const int kappa = 32 * ((4 * v_kg) >> 5) + 8 * (((4 * v_kg) & 15) >> 2) + 4 * (((4 * v_kg) & 31) >> 4);
 
-    uint4 raw[4];
+    constexpr int kLoads = 4;                                  // both roles issue <= 4 loads per tile
+    uint4 raw[kLoads];
     auto prefetch = [&](int j0) {
         const int rem = n - j0;
+        const uint16_t* src = fill_src + (int64_t)j0 * tok;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int key = fills_k ? fill_kg + 16 * a : 4 * fill_kg + a;
+        for (int a = 0; a < kLoads; ++a) {
             raw[a] = make_uint4(0, 0, 0, 0);                   // keys past n are zero in LDS
-            if (key < rem) raw[a] = *reinterpret_cast<const uint4*>(fill_src + (j0 + key) * tok);
+            if (fills_k && a >= kKLoads) continue;
+            if (rem >= kBN || fill_key0 + fill_dkey * a < rem) {
+                if (WAVES == 4 || fills_k) {
+                    raw[a] = *reinterpret_cast<const uint4*>(src + a * fill_step);
+                } else {
+                    const uint2 two = *reinterpret_cast<const uint2*>(src + a * fill_step);
+                    raw[a].x = two.x;
+                    raw[a].y = two.y;
+                }
+            }
         }
     };
     auto stage = [&](int buf) {
         if (fills_k) {
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-                *reinterpret_cast<uint4*>(&k_lds[buf][(fill_kg + 16 * a) * kLdsStride + 8 * fill_dc]) = raw[a];
+            for (int a = 0; a < kKLoads; ++a)
+                *reinterpret_cast<uint4*>(
+                    &k_lds[buf][((fill >> 3) + kKeyStep * a) * kLdsStride + 8 * (fill & 7)]) = raw[a];
         } else {
-            // keys 4*fill_kg .. +3 occupy 4 consecutive kappa slots
-            const int key0 = 4 * fill_kg;
-            const int kappa = 32 * (key0 >> 5) + 8 * ((key0 & 15) >> 2) + 4 * ((key0 & 31) >> 4);
+            constexpr int kDims = (WAVES == 4) ? 8 : 4;        // head-dim elements this thread transposes
             const uint32_t w[4][4] = {{raw[0].x, raw[0].y, raw[0].z, raw[0].w},
                                       {raw[1].x, raw[1].y, raw[1].z, raw[1].w},
                                       {raw[2].x, raw[2].y, raw[2].z, raw[2].w},
                                       {raw[3].x, raw[3].y, raw[3].z, raw[3].w}};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int d = 8 * fill_dc + e;
+            for (int e = 0; e < kDims; ++e) {
+                const int d = v_d0 + e;
                 const int rho = (d & 3) * 16 + (d >> 2);
                 uint2 packed4;
                 if (e & 1) {
@@ -305,7 +335,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const vec8 q_frag[2] = {as_vec8<vec8>(q_raw[0]), as_vec8<vec8>(q_raw[1])};
 
     float m_run = -INFINITY;                                   // running max (log2 domain)
-    float l_run = 0.f;                                         // running sum, this lane's keys only
+    f32x4 l_acc = f32x4{0.f, 0.f, 0.f, 0.f};                   // running row sum (every register equal)
     f32x4 o_acc[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) o_acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -318,18 +348,25 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         if (t + 1 < tiles) prefetch((t + 1) * kBN);
         if (wave_active) {
             const int rem = n - t * kBN;
-            if (rem >= kBN)
-                tile_update<In, true>(k_lds[buf], vt_lds[buf], q_frag, rem, col, g, scale_log2e, m_run, l_run, o_acc);
-            else
-                tile_update<In, false>(k_lds[buf], vt_lds[buf], q_frag, rem, col, g, scale_log2e, m_run, l_run, o_acc);
+            const uint16_t* kt_ = k_lds[buf];
+            const uint16_t* vt_ = vt_lds[buf];
+            if (rem >= kBN) {
+                tile_update<In, 4, false>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc);
+            } else {
+                switch ((rem + 15) >> 4) {
+                    case 1: tile_update<In, 1, true>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc); break;
+                    case 2: tile_update<In, 2, true>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc); break;
+                    case 3: tile_update<In, 3, true>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc); break;
+                    default: tile_update<In, 4, true>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc); break;
+                }
+            }
         }
     }
 
     // ---- normalise and store: this lane owns d = 16g + 4r + dt of its query
     if (wave_active) {
-        const float l_tot = quad_sum(l_run);
         if (q_row < n) {
-            const float inv = 1.0f / l_tot;
+            const float inv = 1.0f / l_acc[0];
             float out16[16];
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
@@ -340,17 +377,32 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
 }
 
+// Rows of Q handled by one work-group for a given upper bound on the sequence lengths: 64 (four
+// wavefronts) when every sequence fits one tile, 128 (eight wavefronts) otherwise -- longer
+// sequences then fill each K/V tile into LDS half as often per query.
+inline int group_rows(int max_seqlen) { return max_seqlen <= 64 ? 64 : 128; }
+
 template <typename In, typename OutT>
 hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
                         const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
                         hipStream_t stream) {
-    const int q_tiles = (max_seqlen + kBM - 1) / kBM;
+    const int rows = group_rows(max_seqlen);
+    const int q_tiles = (max_seqlen + rows - 1) / rows;
     const int pairs = B * H;
     const int pairs8 = (pairs + kXcds - 1) / kXcds * kXcds;
-    hipLaunchKernelGGL((attn_kernel<In, OutT>), dim3(q_tiles * pairs8), dim3(kBlockThreads), 0, stream,
-                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
-                       static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, H,
-                       pairs, pairs8, fabsf(scale) * kLog2e, scale < 0.f ? 1 : 0);
+    const float c = fabsf(scale) * kLog2e;
+    const int neg = scale < 0.f ? 1 : 0;
+    if (rows == 64) {
+        hipLaunchKernelGGL((attn_kernel<In, OutT, 4>), dim3(q_tiles * pairs8), dim3(256), 0, stream,
+                           static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                           static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, H,
+                           pairs, pairs8, c, neg);
+    } else {
+        hipLaunchKernelGGL((attn_kernel<In, OutT, 8>), dim3(q_tiles * pairs8), dim3(512), 0, stream,
+                           static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                           static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, H,
+                           pairs, pairs8, c, neg);
+    }
     return hipGetLastError();
 }
 
