@@ -37,8 +37,8 @@ int ragged_attn(const void* q, const void* k, const void* v, void* o,
                 float scale, ragged_dtype in_dt, ragged_dtype out_dt, void* stream) {
     if (!q || !k || !v || !o || !cu_seqlens) return RAGGED_ERR_NULL;
     if (B <= 0 || H <= 0 || D <= 0 || max_seqlen < 1) return RAGGED_ERR_SHAPE;
-    // grid = q-tiles * (B*H rounded up to a multiple of 8) work-groups must fit a 32-bit grid
-    const int64_t groups = (((int64_t)B * H + 7) / 8 * 8) * (((int64_t)max_seqlen + 63) / 64);
+    // grid <= q-tiles * (B*H rounded up to a whole dispatch batch of 512) must fit a 32-bit grid
+    const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)max_seqlen + 63) / 64);
     if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
     if (D != 64) return RAGGED_ERR_UNSUPPORTED;
     const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
