@@ -15,33 +15,85 @@ __device__ __forceinline__ int nonzero_bytes(uint32_t w) {
     return __popc(t & 0x80808080u);
 }
 
+// Sum over the 64 lanes of a wavefront, result in every lane, without going through LDS: four
+// rotations inside each 16-lane row (DPP row_ror 8/4/2/1), then the gfx950 lane-swap instructions
+// across rows.  permlane16_swap(a, b) returns {a.row0,b.row0,a.row2,b.row2} and
+// {a.row1,b.row1,a.row3,b.row3}; permlane32_swap(a, b) returns {a.lo|b.lo} and {a.hi|b.hi}.  The
+// second operand is a copy made through an opaque move so it can never share a register with the
+// first (the instruction swaps its operands in place).
+template <int kCtrl>
+__device__ __forceinline__ int dpp_move(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xf, 0xf, true);
+}
+__device__ __forceinline__ int opaque_copy(int x) {
+    int y;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(y) : "v"(x));
+    return y;
+}
 __device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWaveSize);
-    return v;
+    v += dpp_move<0x128>(v);                                   // row_ror:8
+    v += dpp_move<0x124>(v);                                   // row_ror:4
+    v += dpp_move<0x122>(v);                                   // row_ror:2
+    v += dpp_move<0x121>(v);                                   // row_ror:1
+    const auto a = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)opaque_copy(v), false, false);
+    const unsigned a0 = a[0], a1 = a[1];
+    v = (int)(a0 + a1);
+    const auto b = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)opaque_copy(v), false, false);
+    const unsigned b0 = b[0], b1 = b[1];
+    return (int)(b0 + b1);
 }
 
-// Work-group-wide count of nonzero bytes in base[0, len).  Every thread of the 256-thread group
-// must call it; every thread receives the total.  The bulk is read as aligned 16-byte words; the
-// unaligned head and the tail go byte by byte, so no byte outside [0, len) is ever touched.
-__device__ int block_count_nonzero(const uint8_t* __restrict__ base, int len, int* lds4) {
+// Work-group-wide count of nonzero bytes in base[0, len), in two halves so that a caller can put
+// other memory traffic between them: prefix_issue() starts the loads (first 16 KB of the range into
+// registers), prefix_finish() consumes them, handles any remainder, and reduces over the group.
+// Every thread of the 256-thread group must call both; every thread receives the total.  The bulk
+// is read as aligned 16-byte words; the unaligned head and the tail go byte by byte, so no byte
+// outside [0, len) is ever touched.
+constexpr int kPrefixWords = 4;    // 16-byte words per thread kept in flight: 16 KB per pass of the group
+
+struct PrefixLoads {
+    uint4 w[kPrefixWords];   // words tid + 256*j of the aligned body (zero if absent)
+    uint8_t hb, tb;          // one head byte / one tail byte (zero if absent)
+    int head, body;
+};
+
+__device__ __forceinline__ PrefixLoads prefix_issue(const uint8_t* __restrict__ base, int len) {
     const int tid = threadIdx.x;
-    int count = 0;
+    PrefixLoads p;
     const int mis = (int)((uintptr_t)base & 15u);
-    int head = mis ? 16 - mis : 0;
-    if (head > len) head = len;
-    if (tid < head) count += base[tid] != 0;
-    const int body = (len - head) >> 4;                       // whole 16-byte words
-    const uint4* words = reinterpret_cast<const uint4*>(base + head);
-    for (int w = tid; w < body; w += kBlockThreads) {
-        const uint4 v = words[w];
-        count += nonzero_bytes(v.x) + nonzero_bytes(v.y) + nonzero_bytes(v.z) + nonzero_bytes(v.w);
+    p.head = mis ? 16 - mis : 0;
+    if (p.head > len) p.head = len;
+    p.body = (len - p.head) >> 4;                             // whole 16-byte words
+    const uint4* words = reinterpret_cast<const uint4*>(base + p.head);
+#pragma unroll
+    for (int j = 0; j < kPrefixWords; ++j)
+        p.w[j] = tid + j * kBlockThreads < p.body ? words[tid + j * kBlockThreads] : make_uint4(0u, 0u, 0u, 0u);
+    p.hb = tid < p.head ? base[tid] : (uint8_t)0;
+    const int tail0 = p.head + (p.body << 4);
+    p.tb = tail0 + tid < len ? base[tail0 + tid] : (uint8_t)0;   // fewer than 16 tail bytes
+    return p;
+}
+
+__device__ __forceinline__ int count_word(uint4 v) {
+    return nonzero_bytes(v.x) + nonzero_bytes(v.y) + nonzero_bytes(v.z) + nonzero_bytes(v.w);
+}
+
+__device__ int prefix_finish(const uint8_t* __restrict__ base, const PrefixLoads& p, int* lds4) {
+    const int tid = threadIdx.x;
+    int count = (p.hb != 0) + (p.tb != 0);
+#pragma unroll
+    for (int j = 0; j < kPrefixWords; ++j) count += count_word(p.w[j]);
+    const uint4* words = reinterpret_cast<const uint4*>(base + p.head);
+    for (int w0 = tid + kPrefixWords * kBlockThreads; w0 < p.body; w0 += kPrefixWords * kBlockThreads) {
+        uint4 more[kPrefixWords];                             // all loads of a pass issued before any is used
+#pragma unroll
+        for (int j = 0; j < kPrefixWords; ++j)
+            more[j] = w0 + j * kBlockThreads < p.body ? words[w0 + j * kBlockThreads] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int j = 0; j < kPrefixWords; ++j) count += count_word(more[j]);
     }
-    const int tail0 = head + (body << 4);
-    if (tail0 + tid < len) count += base[tail0 + tid] != 0;   // fewer than 16 tail bytes
     count = wave_sum(count);
-    __syncthreads();                                          // lds4 may still be read by a prior call
-    if ((tid & (kWaveSize - 1)) == 0) lds4[tid >> 6] = count;
+    if ((tid & (kWaveSize - 1)) == 0) lds4[tid >> 6] = count; // lds4 is used once per kernel
     __syncthreads();
     return lds4[0] + lds4[1] + lds4[2] + lds4[3];
 }
@@ -58,6 +110,9 @@ __device__ __forceinline__ void wave_copy_row(const uint4* __restrict__ src, uin
 //   ballot = keep bits of the chunk; the k-th set bit goes to packed row P + k
 // The last chunk of image i also writes cu_seqlens[i+1]; group 0 writes cu_seqlens[0].
 // ------------------------------------------------------------------------------------------------
+constexpr int kMaxEarly = 4;    // rows a wavefront may hold in registers (EARLY needs chunk <= 16)
+
+template <bool EARLY>
 __global__ __launch_bounds__(kBlockThreads)
 void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, int N, int units,
                  uint4* __restrict__ packed, int64_t cap_rows, int32_t* __restrict__ cu_seqlens,
@@ -70,12 +125,39 @@ void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, 
     const int wave = threadIdx.x >> 6;
     const int row0 = i * N + t0;                               // flat index of the chunk's first token
 
-    const int P = block_count_nonzero(keep, row0, lds4);
+    // Three dependent fabric round trips (mask prefix -> chunk mask -> rows) are folded into two:
+    // the chunk's own mask bytes and the prefix words are requested together, and the source rows
+    // -- which depend only on the chunk's bits, not on the destination -- are requested before the
+    // prefix count is reduced.  Every wavefront reads the chunk's <= 64 mask bytes itself.
+    const bool in_chunk = lane < chunk && t0 + lane < N;
+    const uint8_t my_keep = in_chunk ? keep[row0 + lane] : (uint8_t)0;
+    const PrefixLoads prefix = prefix_issue(keep, row0);
 
-    // Every wavefront reads the chunk's <= 64 mask bytes itself: cheaper than a broadcast via LDS.
-    const bool mine = lane < chunk && t0 + lane < N && keep[row0 + lane] != 0;
+    const bool mine = my_keep != 0;
     const uint64_t bits = __ballot(mine);
-    const int in_chunk = __popcll(bits);
+    const int in_chunk_count = __popcll(bits);
+
+    // Rows of the chunk are dealt to the four wavefronts round-robin: set bit k -> wavefront k%4.
+    // EARLY (chunk <= 16 and rows of at most 128 16-byte words): a wavefront has at most four rows
+    // of two words per lane and requests them now, into registers.
+    uint4 held[kMaxEarly][2];
+    if (EARLY) {
+#pragma unroll
+        for (int r = 0; r < kMaxEarly; ++r) {
+            held[r][0] = make_uint4(0u, 0u, 0u, 0u);
+            held[r][1] = make_uint4(0u, 0u, 0u, 0u);
+            const int k = wave + 4 * r;                        // this wavefront's r-th row is set bit k
+            if (k < in_chunk_count) {
+                uint64_t m = bits;
+                for (int z = 0; z < k; ++z) m &= m - 1;        // drop the k lowest set bits (k < 16)
+                const uint4* src = x + (int64_t)(row0 + __builtin_ctzll(m)) * units;
+                if (lane < units) held[r][0] = src[lane];
+                if (lane + kWaveSize < units) held[r][1] = src[lane + kWaveSize];
+            }
+        }
+    }
+
+    const int P = prefix_finish(keep, prefix, lds4);           // kept tokens before this chunk in the batch
 
     if (wave == 0) {
         if (mine) {
@@ -84,19 +166,30 @@ void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, 
         }
         if (lane == 0) {
             if (blockIdx.x == 0) cu_seqlens[0] = 0;
-            if (c == chunks_per_image - 1) cu_seqlens[i + 1] = P + in_chunk;
+            if (c == chunks_per_image - 1) cu_seqlens[i + 1] = P + in_chunk_count;
         }
     }
 
-    // Rows of the chunk are dealt to the four wavefronts round-robin.
-    uint64_t rest = bits;
-    for (int k = 0; rest != 0; ++k) {
-        const int t = __builtin_ctzll(rest);
-        rest &= rest - 1;
-        if ((k & 3) != wave) continue;
-        const int64_t dst = (int64_t)P + k;
-        if (dst >= cap_rows) break;
-        wave_copy_row(x + (int64_t)(row0 + t) * units, packed + dst * units, units, lane);
+    if (EARLY) {
+#pragma unroll
+        for (int r = 0; r < kMaxEarly; ++r) {
+            const int64_t dst = (int64_t)P + wave + 4 * r;     // r-th row of this wavefront is set bit wave + 4r
+            if (wave + 4 * r < in_chunk_count && dst < cap_rows) {
+                uint4* out = packed + dst * units;
+                if (lane < units) out[lane] = held[r][0];
+                if (lane + kWaveSize < units) out[lane + kWaveSize] = held[r][1];
+            }
+        }
+    } else {
+        uint64_t rest = bits;
+        for (int k = 0; rest != 0; ++k) {
+            const int t = __builtin_ctzll(rest);
+            rest &= rest - 1;
+            if ((k & 3) != wave) continue;
+            const int64_t dst = (int64_t)P + k;
+            if (dst >= cap_rows) break;
+            wave_copy_row(x + (int64_t)(row0 + t) * units, packed + dst * units, units, lane);
+        }
     }
 }
 
@@ -141,7 +234,9 @@ void unpack_fill_kernel(const uint4* __restrict__ src, const uint8_t* __restrict
     const int wave = threadIdx.x >> 6;
     const int row0 = i * N + t0;
 
-    const int rank0 = block_count_nonzero(keep + (int64_t)i * N, t0, lds4);
+    const uint8_t* image_mask = keep + (int64_t)i * N;
+    const PrefixLoads prefix = prefix_issue(image_mask, t0);
+    const int rank0 = prefix_finish(image_mask, prefix, lds4);
     const int64_t base = (int64_t)cu_seqlens[i] + rank0;
 
     const bool valid = lane < chunk && t0 + lane < N;
@@ -170,9 +265,12 @@ hipError_t launch_pack(const void* x, const uint8_t* keep, int B, int N, int C, 
                        hipStream_t stream) {
     const int chunk = pick_chunk(B, N);
     const int cpi = (N + chunk - 1) / chunk;
-    hipLaunchKernelGGL(pack_kernel, dim3(B * cpi), dim3(kBlockThreads), 0, stream,
-                       static_cast<const uint4*>(x), keep, N, C / 8, static_cast<uint4*>(packed),
-                       cap_rows, cu_seqlens, gather_idx, chunk, cpi);
+    // the early-load variant keeps the first 16 KB of mask prefix in registers; beyond that the
+    // remaining prefix loads would queue behind the row loads, so larger masks take the plain order
+    const bool early = chunk <= 4 * kMaxEarly && C / 8 <= 2 * kWaveSize && (int64_t)B * N <= 16384;
+    hipLaunchKernelGGL(early ? pack_kernel<true> : pack_kernel<false>, dim3(B * cpi),
+                       dim3(kBlockThreads), 0, stream, static_cast<const uint4*>(x), keep, N, C / 8,
+                       static_cast<uint4*>(packed), cap_rows, cu_seqlens, gather_idx, chunk, cpi);
     return hipGetLastError();
 }
 
