@@ -129,5 +129,54 @@ def ragged_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream
     _check("ragged_unpack", st)
 
 
+class Prepared:
+    """A call with its arguments marshalled once: ``prepared()`` re-issues the same launch on the
+    stream it was prepared for, skipping the per-call tensor checks (serving loops re-launch the same
+    buffers every step, and at ViT sizes the host-side dispatch cost is what the caller sees).
+    The tensors must stay alive and in place for as long as the object is used."""
+
+    __slots__ = ("_fn", "_args", "_name", "_keepalive")
+
+    def __init__(self, name, fn, args, keepalive):
+        self._name, self._fn, self._args, self._keepalive = name, fn, args, keepalive
+
+    def __call__(self) -> None:
+        st = self._fn(*self._args)
+        if st != RAGGED_OK:
+            raise RaggedError(self._name, st)
+
+
+def prepare_pack(x, keep, packed, cu_seqlens, gather_idx, stream=None) -> Prepared:
+    B, N, C = x.shape
+    cap = packed.shape[0]
+    args = (_dev(x, "x", (torch.float16, torch.bfloat16)),
+            _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)), B, N, C, _DTYPE_CODE[x.dtype],
+            _dev(packed, "packed", x.dtype, (cap, C)), cap,
+            _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
+            _dev(gather_idx, "gather_idx", torch.int32, (cap,)), _stream(stream))
+    return Prepared("ragged_pack", load().ragged_pack, args, (x, keep, packed, cu_seqlens, gather_idx))
+
+
+def prepare_attn(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=None) -> Prepared:
+    rows, H, D = q.shape
+    B = cu_seqlens.shape[0] - 1
+    args = (_dev(q, "q", (torch.float16, torch.bfloat16)), _dev(k, "k", q.dtype, q.shape),
+            _dev(v, "v", q.dtype, q.shape), _dev(o, "o", (q.dtype, torch.float32), q.shape),
+            _dev(cu_seqlens, "cu_seqlens", torch.int32), B, int(max_seqlen), H, D, float(scale),
+            _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], _stream(stream))
+    return Prepared("ragged_attn", load().ragged_attn, args, (q, k, v, o, cu_seqlens))
+
+
+def prepare_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> Prepared:
+    B, N, C = out.shape
+    args = (_dev(src, "src", (torch.float16, torch.bfloat16)),
+            None if keep is None else _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)),
+            _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
+            None if gather_idx is None else _dev(gather_idx, "gather_idx", torch.int32),
+            B, N, C, _DTYPE_CODE[src.dtype], _dev(out, "out", src.dtype), int(fill_mode),
+            _stream(stream))
+    return Prepared("ragged_unpack", load().ragged_unpack, args, (src, keep, cu_seqlens, gather_idx, out))
+
+
 def ragged_noop(grid: int, stream=None) -> None:
     _check("ragged_noop", load().ragged_noop(int(grid), _stream(stream)))
