@@ -1,0 +1,171 @@
+"""Measurement plumbing shared by ``bench.py`` and ``paper_2604_15408_amd.suite``: device buffers for a
+workload, the three stage calls, HIP-graph capture and event timing.  No arithmetic of the method.
+"""
+from __future__ import annotations
+
+import statistics
+import time
+
+REPLICAS = 20                    # copies of one kernel inside a graph when timing that kernel alone
+
+
+def make_workload(name: str):
+    from paper_2604_15408_amd import workloads as wl
+    if name == "headline":
+        return wl.deit_b_pruned(0.2, 32, "f16", 1001)
+    if name == "tiny":
+        return wl.tiny()
+    if name.startswith("keep"):                       # e.g. keep0.6 : bf16 sweep point
+        p = float(name[4:])
+        k = wl.SWEEP_KEEP_PROBS.index(p)
+        return wl.sweep()[k]
+    if name.startswith("serving"):                    # e.g. serving4
+        return wl.serving_384(int(name[7:]))
+    if name.startswith("layer"):                      # e.g. layer1 : pipeline layer (B=64)
+        return wl.pipeline()[int(name[5:]) - 1]
+    raise SystemExit(f"unknown workload {name!r}")
+
+
+class Path:
+    """Device buffers of one workload plus the three stage calls."""
+
+    def __init__(self, w, fill_mode: int = 0):
+        import torch
+        from paper_2604_15408_amd import binding
+        self.torch, self.b, self.w, self.fill_mode = torch, binding, w, fill_mode
+        dev = "cuda:0"
+        B, N, C, H, D = w.B, w.N, w.C, w.H, w.D
+        self.T = w.T
+        rows = max(self.T, 1)
+        self.x = w.features().to(dev)
+        self.keep = w.keep.to(dev)
+        self.packed = torch.zeros(B * N, C, dtype=self.x.dtype, device=dev)
+        self.cu = torch.zeros(B + 1, dtype=torch.int32, device=dev)
+        self.gidx = torch.zeros(B * N, dtype=torch.int32, device=dev)
+        q, k, v = w.qkv(rows)
+        self.q, self.k, self.v = q.to(dev), k.to(dev), v.to(dev)
+        self.o = torch.zeros(rows, H, D, dtype=self.q.dtype, device=dev)
+        self.out = torch.zeros(B, N, C, dtype=self.x.dtype, device=dev)
+        torch.cuda.synchronize()
+
+    def pack(self):
+        self.b.ragged_pack(self.x, self.keep, self.packed, self.cu, self.gidx)
+
+    def attn(self):
+        # max_seqlen = N: nothing about the lengths is known on the host (no sync after pack)
+        self.b.ragged_attn(self.q, self.k, self.v, self.o, self.cu, self.w.N, self.w.scale)
+
+    def unpack(self):
+        self.b.ragged_unpack(self.o.view(-1, self.w.C), self.keep, self.cu, self.gidx, self.out,
+                             self.fill_mode)
+
+    def step(self):
+        self.pack()
+        self.attn()
+        self.unpack()
+
+    def prepared_step(self):
+        """The same three launches with arguments marshalled once (binding.Prepared), bound to the
+        current stream: what a serving loop that re-launches fixed buffers would call."""
+        b, w = self.b, self.w
+        calls = (b.prepare_pack(self.x, self.keep, self.packed, self.cu, self.gidx),
+                 b.prepare_attn(self.q, self.k, self.v, self.o, self.cu, w.N, w.scale),
+                 b.prepare_unpack(self.o.view(-1, w.C), self.keep, self.cu, self.gidx, self.out,
+                                  self.fill_mode))
+
+        def step():
+            for call in calls:
+                call()
+        return step
+
+    # algorithmic bytes / flops of one launch of each stage (what the method itself must move)
+    def algorithmic(self):
+        w, T = self.w, self.T
+        row = w.C * 2
+        sq = sum(n * n for n in w.lengths)
+        unpack_bytes = 2 * T * row + 4 * T if self.fill_mode == 0 else T * row + w.B * w.N * row + w.B * w.N
+        return {
+            "pack": {"bytes": w.B * w.N + 2 * T * row + 4 * (w.B + 1) + 4 * T},
+            "attn": {"bytes": 4 * T * row, "flops": 4 * w.D * w.H * sq},
+            "unpack": {"bytes": unpack_bytes},
+        }
+
+
+def capture(torch, fn, reps: int = 1):
+    """Record `reps` calls of fn into one HIP graph (side stream, torch's capture plumbing)."""
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        fn()                                          # warm the code path outside capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            for _ in range(reps):
+                fn()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    return g
+
+
+def event_time_us(torch, launch, iters: int, warmup: int = 5):
+    """Median / mean GPU time of launch() in microseconds, HIP events on the launching stream."""
+    for _ in range(warmup):
+        launch()
+    torch.cuda.synchronize()
+    samples = []
+    for _ in range(iters):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        launch()
+        e1.record()
+        e1.synchronize()
+        samples.append(e0.elapsed_time(e1) * 1e3)
+    return statistics.median(samples), statistics.fmean(samples)
+
+
+def wall_steps(torch, fn, steps: int):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+class Pipeline:
+    """The 12-layer progressive-pruning loop (B=64, N=197, C=768): per layer
+    pack(X_l, mask_l) -> ragged_attn(Q_l, K_l, V_l; cu_seqlens from pack) -> unpack(O_l) -> X_{l+1}.
+    There are no projection weights, so Q/K/V of every layer are seeded N(0,1) tensors of that
+    layer's packed length; pack's row output is produced (and parity-checked in the tests) but feeds
+    nothing downstream.  All 36 launches use upper-bound grids, so the loop is graph-capturable."""
+
+    def __init__(self, layers, fill_mode: int = 1):
+        import torch
+        from paper_2604_15408_amd import binding
+        self.torch, self.b, self.layers, self.fill_mode = torch, binding, layers, fill_mode
+        dev = "cuda:0"
+        w0 = layers[0]
+        B, N, C, H, D = w0.B, w0.N, w0.C, w0.H, w0.D
+        self.x = [w0.features().to(dev)] + [torch.zeros(B, N, C, dtype=torch.float16, device=dev)
+                                            for _ in layers]
+        self.keep = [w.keep.to(dev) for w in layers]
+        self.packed = torch.zeros(B * N, C, dtype=torch.float16, device=dev)
+        self.cu = [torch.zeros(B + 1, dtype=torch.int32, device=dev) for _ in layers]
+        self.gidx = [torch.zeros(B * N, dtype=torch.int32, device=dev) for _ in layers]
+        self.qkv = [tuple(t.to(dev) for t in w.qkv(max(w.T, 1))) for w in layers]
+        self.o = [torch.zeros(max(w.T, 1), H, D, dtype=torch.float16, device=dev) for w in layers]
+        torch.cuda.synchronize()
+
+    def run(self):
+        b = self.b
+        for l, w in enumerate(self.layers):
+            q, k, v = self.qkv[l]
+            b.ragged_pack(self.x[l], self.keep[l], self.packed, self.cu[l], self.gidx[l])
+            b.ragged_attn(q, k, v, self.o[l], self.cu[l], w.N, w.scale)
+            b.ragged_unpack(self.o[l].view(-1, w.C), self.keep[l], self.cu[l], self.gidx[l],
+                            self.x[l + 1], self.fill_mode)
+
+    @property
+    def tokens(self) -> int:
+        return sum(w.T for w in self.layers)

@@ -1,0 +1,108 @@
+"""Measure every benchmark configuration on one MI355X and print one JSON line per case.
+
+    python -m paper_2604_15408_amd.suite [--out gpurun_out/suite.jsonl]
+
+Cases: the headline batch; the bf16 pruning-ratio sweep next to a padded baseline of the same shape
+(this library's own attention kernel run with every image at the full N tokens -- the bytes and
+flops a padded dense attention has to spend, with no mask cost added); the 384x384 serving batches;
+the 12-layer progressive-pruning loop captured in ONE HIP graph.  Kernel times are HIP-event times
+of a graph holding 20 back-to-back copies of the kernel (divided by 20), so they include the
+in-graph kernel-to-kernel gap that an empty kernel shows separately.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+from . import workloads as wl
+from .harness import REPLICAS, Path, Pipeline, capture, event_time_us, wall_steps
+
+
+def stage_times(torch, p: Path):
+    out = {}
+    for name, fn in (("pack", p.pack), ("attn", p.attn), ("unpack", p.unpack)):
+        g = capture(torch, fn, REPLICAS)
+        out[name] = event_time_us(torch, g.replay, iters=30)[0] / REPLICAS
+    return out
+
+
+def case(torch, w, label: str):
+    p = Path(w, 0)
+    alg = p.algorithmic()
+    us = stage_times(torch, p)
+    g = capture(torch, p.step)
+    step_graph = wall_steps(torch, g.replay, 300) * 1e6
+    lean = p.prepared_step()
+    step_lean = wall_steps(torch, lean, 300) * 1e6
+    return {"case": label, "workload": w.name, "dtype": w.dtype, "B": w.B, "N": w.N, "T": w.T,
+            "max_len": max(w.lengths), "kernel_us": us,
+            "gbs": {k: alg[k]["bytes"] / (us[k] * 1e-6) / 1e9 for k in us},
+            "attn_tflops": alg["attn"]["flops"] / (us["attn"] * 1e-6) / 1e12,
+            "attn_tokens_per_s": w.T / (us["attn"] * 1e-6),
+            "step_us": {"hipgraph": step_graph, "eager_prepared": step_lean},
+            "step_tokens_per_s": w.T / (min(step_graph, step_lean) * 1e-6)}
+
+
+def padded_baseline(torch, w):
+    """Attention time if every image kept all N tokens (what padding to N costs)."""
+    full = wl.deit_b_pruned(1.0, w.B, w.dtype, w.seed)
+    p = Path(full, 0)
+    p.pack()
+    torch.cuda.synchronize()
+    g = capture(torch, p.attn, REPLICAS)
+    return event_time_us(torch, g.replay, iters=30)[0] / REPLICAS
+
+
+def pipeline_case(torch):
+    layers = wl.pipeline()
+    pipe = Pipeline(layers, fill_mode=1)
+    pipe.run()
+    torch.cuda.synchronize()
+    g = capture(torch, pipe.run)
+    us_graph = event_time_us(torch, g.replay, iters=30)[0]
+    wall_graph = wall_steps(torch, g.replay, 100) * 1e6
+    wall_eager = wall_steps(torch, pipe.run, 100) * 1e6
+    return {"case": "pipeline_12_layers", "B": layers[0].B, "N": layers[0].N,
+            "T_per_layer": [w.T for w in layers], "tokens": pipe.tokens, "kernels_in_graph": 36,
+            "graph_gpu_us": us_graph, "graph_wall_us": wall_graph, "eager_wall_us": wall_eager,
+            "tokens_per_s": pipe.tokens / (wall_graph * 1e-6)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default=None)
+    args = ap.parse_args()
+    import torch
+    from . import binding
+    if not torch.cuda.is_available():
+        raise SystemExit("the suite needs a GPU")
+    binding.load()
+    lines = []
+
+    def emit(rec):
+        lines.append(rec)
+        print(json.dumps(rec), flush=True)
+
+    emit(case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "headline"))
+    pad_us = None
+    for w in wl.sweep():
+        rec = case(torch, w, "sweep")
+        if pad_us is None:
+            pad_us = padded_baseline(torch, w)
+        rec["padded_attn_us"] = pad_us
+        rec["attn_speedup_vs_padded"] = pad_us / rec["kernel_us"]["attn"]
+        emit(rec)
+    for B in (1, 2, 4, 32):
+        emit(case(torch, wl.serving_384(B), "serving_384"))
+    emit(pipeline_case(torch))
+    if args.out:
+        os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
+        with open(args.out, "w") as f:
+            for rec in lines:
+                f.write(json.dumps(rec) + "\n")
+
+
+if __name__ == "__main__":
+    sys.exit(main())

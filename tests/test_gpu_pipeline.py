@@ -1,0 +1,76 @@
+"""The whole pipeline inside HIP graphs: every entry point must be capturable (no allocation, no
+synchronisation, no host read), and replays must reproduce the eager result bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_15408_amd import workloads as wl
+from paper_2604_15408_amd.harness import Path, Pipeline, capture
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+def _small_pipeline(B=6):
+    masks = wl.pipeline_masks(B=B, seed=77)
+    return [wl.Workload(f"pipe{l}", B, 197, 12, 64, "f16", 500 + l, m) for l, m in enumerate(masks)]
+
+
+def test_single_step_graph_replays_match_eager():
+    w = wl.deit_b_pruned(0.3, B=8)
+    p = Path(w, fill_mode=1)
+    p.step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (p.packed, p.cu, p.gidx, p.o, p.out)]
+    g = capture(torch, p.step)
+    for rep in range(4):
+        for t in (p.packed, p.o, p.out):
+            t.fill_(-3.0)                                   # eager work between the replays
+        p.cu.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        T = int(p.cu[-1])
+        assert T == w.T
+        assert torch.equal(p.cu, want[1])
+        assert torch.equal(p.gidx[:T], want[2][:T])
+        assert torch.equal(p.packed[:T].view(torch.int16), want[0][:T].view(torch.int16))
+        assert torch.equal(p.o[:T].view(torch.int16), want[3][:T].view(torch.int16))
+        assert torch.equal(p.out.view(torch.int16), want[4].view(torch.int16))
+
+
+def test_twelve_layer_loop_in_one_graph_matches_eager_and_oracle():
+    layers = _small_pipeline()
+    pipe = Pipeline(layers, fill_mode=1)
+    pipe.run()
+    torch.cuda.synchronize()
+    eager_final = pipe.x[-1].clone()
+    eager_cu = [c.clone() for c in pipe.cu]
+    eager_o = [o.clone() for o in pipe.o]
+
+    g = capture(torch, pipe.run)
+    for rep in range(3):
+        for t in pipe.x[1:]:
+            t.fill_(9.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(pipe.x[-1].view(torch.int16), eager_final.view(torch.int16))
+        for l in range(12):
+            assert torch.equal(pipe.cu[l], eager_cu[l])
+            assert torch.equal(pipe.o[l].view(torch.int16), eager_o[l].view(torch.int16))
+
+    # oracle: lengths of every layer, attention of the last (most pruned) layer, final unpack
+    for l, w in enumerate(layers):
+        assert pipe.cu[l].cpu().numpy().tolist() == hp.cu_from_lengths(w.lengths).tolist()
+    w = layers[-1]
+    q, k, v = w.qkv()
+    cu = hp.cu_from_lengths(w.lengths)
+    want_o = oracle.attn(wl.to_words(q), wl.to_words(k), wl.to_words(v), cu, w.scale, "f16", threads=8)
+    got_o = pipe.o[-1][: w.T].cpu().to(torch.float64).numpy()
+    assert np.max(np.abs(got_o - want_o)) <= 2e-3
+    want_x = oracle.unpack(wl.to_words(pipe.o[-1][: w.T].cpu()).reshape(w.T, w.C), w.keep.numpy(), cu, w.C, 1)
+    assert np.array_equal(wl.to_words(pipe.x[-1].cpu()), want_x)
+    # tokens dropped at an earlier layer stay dropped: their rows are zero after the last unpack
+    assert not pipe.x[-1][~w.keep.bool().to("cuda:0")].any()
