@@ -264,7 +264,11 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     // K thread: 16-byte units (key = fill/8 + kKeyStep*a, dims 8*(fill%8) ..)
     // V thread, WAVES == 4: keys 4*(fill/8)  .. +3, dims 8*(fill%8)  .. +7  (4 x 16-byte loads)
     //           WAVES == 8: keys 4*(fill/16) .. +3, dims 4*(fill%16) .. +3  (4 x  8-byte loads)
-    const int v_kg = (WAVES == 4) ? fill >> 3 : fill >> 4;
+    // The key group of a V thread takes its bit 2 (which 16-key half of a 32-key block, i.e. which
+    // 8-byte half of a 16-byte LDS unit) from lane bit 3, so that the 32 lanes of a half-wavefront
+    // spread their 8-byte transposed writes evenly over all LDS banks.
+    const int v_slot = (WAVES == 4) ? fill >> 3 : fill >> 4;   // 0..15
+    const int v_kg = (v_slot & 8) | ((v_slot & 1) << 2) | ((v_slot >> 1) & 3);
     const int v_d0 = (WAVES == 4) ? 8 * (fill & 7) : 4 * (fill & 15);
     const uint16_t* fill_src = fills_k ? k + (s + (fill >> 3)) * tok + head_off + 8 * (fill & 7)
                                        : v + (s + 4 * v_kg) * tok + head_off + v_d0;
