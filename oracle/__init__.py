@@ -54,6 +54,8 @@ def _load():
         lib.oracle_attn_row.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, i32,
                                         ctypes.c_float, vp, vp]
         lib.oracle_attn_row.restype = i32
+        lib.oracle_attn_padded.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, ctypes.c_float, vp]
+        lib.oracle_attn_padded.restype = i32
         lib.oracle_max_threads.argtypes = []
         lib.oracle_max_threads.restype = i32
         _lib = lib
@@ -170,3 +172,19 @@ def attn_row(q, k, v, cu_seqlens, i: int, h: int, r: int, scale: float, dtype: s
     if rc != 0:
         raise IndexError("row out of range")
     return probs, o
+
+
+def attn_padded(q, k, v, keep, scale: float, dtype: str = "f16") -> np.ndarray:
+    """Attention on the padded layout: q,k,v [B,N,H,D] words, keep [B,N] -> [B,N,H,D] float64 with
+    the kept tokens of each image attending among themselves and +0.0 rows for dropped tokens."""
+    q, k, v = _words(q, 4), _words(k, 4), _words(v, 4)
+    if not (q.shape == k.shape == v.shape):
+        raise ValueError("q, k, v shapes differ")
+    B, N, H, D = q.shape
+    keep = _mask(keep, B, N)
+    out = np.full((B, N, H, D), np.nan, dtype=np.float64)
+    rc = _load().oracle_attn_padded(_ptr(q), _ptr(k), _ptr(v), _DTYPES[dtype], _ptr(keep), B, N, H, D,
+                                    float(scale), _ptr(out))
+    if rc != 0:
+        raise MemoryError("oracle_attn_padded failed to allocate scratch")
+    return out

@@ -252,6 +252,55 @@ int oracle_attn_row(const uint16_t *q, const uint16_t *k, const uint16_t *v, int
     return ok ? 0 : -1;
 }
 
+/*
+ * Attention straight on the padded layout (the single-launch variant of the pipeline, in which the
+ * gather of pack and the scatter of unpack are folded into the attention itself): q, k, v are
+ * [B, N, H, D] 16-bit words, keep is [B, N] bytes, out is [B, N, H, D] doubles.  For every image
+ * the kept tokens, in ascending token order, attend among themselves exactly as in oracle_attn;
+ * nothing is computed for dropped tokens, whose rows of out are set to +0.0.
+ * Written out on its own (index list + the definition), not by calling pack / attn / unpack, so
+ * that the tests can check it against that composition.
+ */
+int oracle_attn_padded(const uint16_t *q, const uint16_t *k, const uint16_t *v, int dtype,
+                       const uint8_t *keep, int B, int N, int H, int D, float scale, double *out)
+{
+    int *idx = (int *)malloc((size_t)(N > 0 ? N : 1) * sizeof(int));
+    double *scores = (double *)malloc((size_t)(N > 0 ? N : 1) * sizeof(double));
+    if (!idx || !scores) { free(idx); free(scores); return -1; }
+    const int64_t tok = (int64_t)H * D;
+    for (int i = 0; i < B; ++i) {
+        int n = 0;
+        for (int t = 0; t < N; ++t) {
+            if (keep[(int64_t)i * N + t] != 0) idx[n++] = t;
+            else for (int64_t e = 0; e < tok; ++e) out[((int64_t)i * N + t) * tok + e] = 0.0;
+        }
+        for (int h = 0; h < H; ++h) {
+            for (int r = 0; r < n; ++r) {
+                const uint16_t *qrow = q + ((int64_t)i * N + idx[r]) * tok + (int64_t)h * D;
+                double M = -INFINITY;
+                for (int j = 0; j < n; ++j) {
+                    const uint16_t *krow = k + ((int64_t)i * N + idx[j]) * tok + (int64_t)h * D;
+                    double dot = 0.0;
+                    for (int d = 0; d < D; ++d) dot += decode(qrow[d], dtype) * decode(krow[d], dtype);
+                    scores[j] = (double)scale * dot;
+                    if (scores[j] > M) M = scores[j];
+                }
+                double L = 0.0;
+                for (int j = 0; j < n; ++j) { scores[j] = exp(scores[j] - M); L += scores[j]; }
+                double *o = out + ((int64_t)i * N + idx[r]) * tok + (int64_t)h * D;
+                for (int d = 0; d < D; ++d) o[d] = 0.0;
+                for (int j = 0; j < n; ++j) {
+                    const uint16_t *vrow = v + ((int64_t)i * N + idx[j]) * tok + (int64_t)h * D;
+                    for (int d = 0; d < D; ++d) o[d] += scores[j] * decode(vrow[d], dtype);
+                }
+                for (int d = 0; d < D; ++d) o[d] /= L;
+            }
+        }
+    }
+    free(idx); free(scores);
+    return 0;
+}
+
 /* Number of OpenMP threads a parallel region would get by default (1 without OpenMP). */
 int oracle_max_threads(void)
 {

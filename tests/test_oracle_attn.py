@@ -277,3 +277,55 @@ def test_fp16_rounding_of_the_oracle_is_within_the_papers_error_band():
     err = np.max(np.abs(out.astype(np.float16).astype(np.float64) - out))
     assert err <= 2 * max(golden["max_abs_diff"].values())
     assert err >= 0.1 * min(golden["max_abs_diff"].values())
+
+
+# ---- attention on the padded layout (pack and unpack folded into the attention) -----------------
+
+def _padded_case(B, N, H, D, p, dtype, seed):
+    keep = wl.keep_bernoulli(B, N, p, seed).numpy()
+    qw, qf = _rand_words((B, N, H, D), dtype, seed + 1)
+    kw, kf = _rand_words((B, N, H, D), dtype, seed + 2)
+    vw, vf = _rand_words((B, N, H, D), dtype, seed + 3)
+    return keep, (qw, kw, vw), (qf, kf, vf)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_padded_attention_equals_pack_attend_unpack(dtype):
+    """The folded variant must equal the composition of the three pinned stages."""
+    B, N, H, D = 3, 13, 2, 8
+    keep, (qw, kw, vw), _ = _padded_case(B, N, H, D, 0.5, dtype, 90)
+    keep[1, :] = 0                                             # an image with nothing kept
+    got = oracle.attn_padded(qw, kw, vw, keep, 0.3, dtype)
+    kb = keep.astype(bool)
+    cu = _cu(keep.sum(axis=1))
+    packed = oracle.attn(qw[kb], kw[kb], vw[kb], cu, 0.3, dtype)
+    want = np.zeros((B, N, H, D))
+    want[kb] = packed
+    assert np.array_equal(got, want)
+
+
+def test_padded_attention_matches_masked_dense_numpy():
+    B, N, H, D = 2, 9, 3, 4
+    keep, (qw, kw, vw), (qf, kf, vf) = _padded_case(B, N, H, D, 0.6, "f16", 91)
+    got = oracle.attn_padded(qw, kw, vw, keep, 0.25, "f16")
+    S = np.einsum("bqhd,bkhd->bhqk", qf, kf) * 0.25
+    S = np.where(keep[:, None, None, :].astype(bool), S, -np.inf)
+    P = np.exp(S - S.max(axis=-1, keepdims=True))
+    P /= P.sum(axis=-1, keepdims=True)
+    O = np.einsum("bhqk,bkhd->bqhd", P, vf)
+    kb = keep.astype(bool)
+    assert np.max(np.abs(got[kb] - O[kb])) < 1e-13
+    assert not got[~kb].any() and np.all(np.isfinite(got))
+
+
+def test_padded_attention_ignores_dropped_tokens_entirely():
+    """Garbage (even NaN patterns) in dropped rows of q, k, v must not reach any output."""
+    B, N, H, D = 2, 10, 2, 4
+    keep, (qw, kw, vw), _ = _padded_case(B, N, H, D, 0.5, "f16", 92)
+    a = oracle.attn_padded(qw, kw, vw, keep, 0.5, "f16")
+    kb = keep.astype(bool)
+    q2, k2, v2 = qw.copy(), kw.copy(), vw.copy()
+    for arr in (q2, k2, v2):
+        arr[~kb] = 0x7E00                                      # fp16 NaN
+    b = oracle.attn_padded(q2, k2, v2, keep, 0.5, "f16")
+    assert np.array_equal(a, b)
