@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA, published
 
 
-from paper_2604_15408_amd.harness import (REPLICAS, Path, capture, event_time_us, make_workload,  # noqa: E402
+from paper_2604_15408_amd.harness import (REPLICAS, PaddedPath, Path, capture, event_time_us, make_workload,  # noqa: E402
                                           wall_steps)
 
 
@@ -92,6 +92,12 @@ def run(args):
     g_pipe = capture(torch, p.step, REPLICAS)
     pipe_us = event_time_us(torch, g_pipe.replay, iters=max(20, args.steps // 10))[0] / REPLICAS
 
+    # ---- the same layer as ONE launch on the padded layout (gather-on-load attention)
+    fused = PaddedPath(w, args.fill_mode)
+    g_fused = capture(torch, fused.run, REPLICAS)
+    fused_kernel_us = event_time_us(torch, g_fused.replay, iters=max(20, args.steps // 10))[0] / REPLICAS
+    fused_wall_us = wall_steps(torch, fused.prepared(), args.steps) * 1e6
+
     # ---- launch floor: an empty kernel, same grid size as the attention launch
     attn_grid = w.B * w.H * ((w.N + 63) // 64)
     noop = lambda: binding.ragged_noop(attn_grid)
@@ -140,6 +146,9 @@ def run(args):
             "step_wall_us": {k: v * 1e6 for k, v in t_modes.items()},
             "attn_mfma_tflops": attn_tflops, "attn_mfma_frac": attn_tflops / MFMA_F16_PEAK_TFLOPS,
             "stage_gbs": {k: alg[k]["bytes"] / (stage_us[k] * 1e-6) / 1e9 for k in stage_us},
+            "fused_single_launch": {"entry": "ragged_attn_padded", "kernel_us": fused_kernel_us,
+                                    "wall_us_per_layer": fused_wall_us,
+                                    "tokens_per_s": w.T / (fused_wall_us * 1e-6)},
             "floor": floor,
             "paper_context": "paper's Triton kernel on RTX 4000 Ada: 24 us attention latency at BS=32, 40 tok/img (uniform lengths)",
         },

@@ -102,6 +102,28 @@ int ragged_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlen
                   void* out, int fill_mode, void* stream);
 
 /*
+ * ragged_attn_padded -- the whole pack-attend-unpack pipeline of Section 4 for ONE attention layer
+ * in ONE launch: the kernel turns each image's keep mask into its list of kept token positions and
+ * reads / writes Q, K, V, O rows through that list, so no packed copy, no cu_seqlens and no gather
+ * index exist.  Same arithmetic as ragged_attn on the packed rows (bit-identical outputs).  The
+ * paper's argument (Section 3 and Section 4.2, "Why dispatch overhead is lower") is that at ViT sizes
+ * the number of dispatches, not the arithmetic, sets the latency; this entry point removes two of
+ * the three.
+ *
+ *   q, k, v    [B, N, H, D]  padded, token-major inside an image (in_dt); rows of dropped tokens are
+ *                            never read
+ *   o          [B, N, H, D]  out (out_dt): rows of kept tokens receive the attention output;
+ *                            fill_mode 0 leaves rows of dropped tokens untouched, 1 writes +0
+ *   keep       [B, N]        one byte per token, any nonzero value = keep
+ *
+ * Supported: D = 64, N <= 1536, the dtype pairs of ragged_attn.  Images with nothing kept produce no
+ * attention rows.
+ */
+int ragged_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
+                       int B, int N, int H, int D, float scale, ragged_dtype in_dt,
+                       ragged_dtype out_dt, int fill_mode, void* stream);
+
+/*
  * ragged_noop -- enqueue an empty kernel of `grid` work-groups of 256 threads on `stream`.
  * It exists to measure the launch floor that Section 3 ("The Dispatch Overhead") is about,
  * separately from the time the real kernels spend on the GPU.

@@ -19,8 +19,8 @@ RAGGED_OK = 0
 RAGGED_F16, RAGGED_BF16, RAGGED_F32 = 0, 1, 2
 _DTYPE_CODE = {torch.float16: RAGGED_F16, torch.bfloat16: RAGGED_BF16, torch.float32: RAGGED_F32}
 
-EXPORTS = ("ragged_pack", "ragged_attn", "ragged_unpack", "ragged_noop", "ragged_status_string",
-           "ragged_version")
+EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_padded", "ragged_unpack", "ragged_noop",
+           "ragged_status_string", "ragged_version")
 
 _lib = None
 
@@ -45,6 +45,8 @@ def load() -> ctypes.CDLL:
         lib.ragged_pack.restype = i32
         lib.ragged_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, vp]
         lib.ragged_attn.restype = i32
+        lib.ragged_attn_padded.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, i32, vp]
+        lib.ragged_attn_padded.restype = i32
         lib.ragged_unpack.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
         lib.ragged_unpack.restype = i32
         lib.ragged_noop.argtypes = [i32, vp]
@@ -115,6 +117,20 @@ def ragged_attn(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=No
     _check("ragged_attn", st)
 
 
+def _attn_padded_args(q, k, v, o, keep, scale, fill_mode, stream):
+    B, N, H, D = q.shape
+    return (_dev(q, "q", (torch.float16, torch.bfloat16)), _dev(k, "k", q.dtype, q.shape),
+            _dev(v, "v", q.dtype, q.shape), _dev(o, "o", (q.dtype, torch.float32), q.shape),
+            _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)), B, N, H, D, float(scale),
+            _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], int(fill_mode), _stream(stream))
+
+
+def ragged_attn_padded(q, k, v, o, keep, scale: float, fill_mode: int = 0, stream=None) -> None:
+    """q,k,v,o [B,N,H,D], keep [B,N]: pack + attention + unpack of one layer in a single launch."""
+    _check("ragged_attn_padded",
+           load().ragged_attn_padded(*_attn_padded_args(q, k, v, o, keep, scale, fill_mode, stream)))
+
+
 def ragged_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> None:
     """src [rows,C] -> out [B,N,C].  fill_mode 0 needs gather_idx (keep may be None); fill_mode 1
     needs keep (gather_idx may be None)."""
@@ -165,6 +181,11 @@ def prepare_attn(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=N
             _dev(cu_seqlens, "cu_seqlens", torch.int32), B, int(max_seqlen), H, D, float(scale),
             _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], _stream(stream))
     return Prepared("ragged_attn", load().ragged_attn, args, (q, k, v, o, cu_seqlens))
+
+
+def prepare_attn_padded(q, k, v, o, keep, scale: float, fill_mode: int = 0, stream=None) -> Prepared:
+    return Prepared("ragged_attn_padded", load().ragged_attn_padded,
+                    _attn_padded_args(q, k, v, o, keep, scale, fill_mode, stream), (q, k, v, o, keep))
 
 
 def prepare_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> Prepared:

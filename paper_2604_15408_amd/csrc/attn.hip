@@ -43,6 +43,7 @@ constexpr int kBN = 64;                 // keys per K/V tile
 constexpr int kLdsStride = 72;          // halves per LDS row: 64 + 8 of padding (144 bytes)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazyLog2 = 8.0f;       // probabilities stay below 2^8 between rescales
+constexpr int kMaxGatherTokens = 1536;  // tokens per image the gather-on-load variant can index in LDS
 
 struct F16 {
     typedef f16x8 vec8;
@@ -221,11 +222,19 @@ __device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
 // tile is computed, so one barrier per tile suffices and the fabric latency of tile t+1 hides
 // behind the arithmetic of tile t.  The lower half of the threads copies K, the upper half
 // transposes V.
-template <typename In, typename OutT, int WAVES>
+//
+// GATHER = false: q, k, v, o are packed [T, H, D] and image i owns rows [cu[i], cu[i+1]).
+// GATHER = true : q, k, v, o are padded [B, N, H, D]; the group first turns image i's keep mask
+//   into the list of kept token positions (ballot + prefix over the group, in LDS) and then reads
+//   and writes rows through that list, so pack and unpack need no launch of their own.  With
+//   fill_mode 1 the q-tile-0 group of every (image, head) also zeroes that head's slice of the
+//   dropped rows of o.
+template <typename In, typename OutT, int WAVES, bool GATHER>
 __global__ __launch_bounds__(kWaveSize * WAVES, 4)
 void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                  const uint16_t* __restrict__ v, OutT* __restrict__ o,
-                 const int32_t* __restrict__ cu_seqlens, int H, int pairs, int q_tiles, int group,
+                 const int32_t* __restrict__ cu_seqlens, const uint8_t* __restrict__ keep, int n_tok,
+                 int fill_mode, int H, int pairs, int q_tiles, int group,
                  float scale_log2e, int negate_q) {
     typedef typename In::vec8 vec8;
     constexpr int kBM = 16 * WAVES;                            // queries per work-group
@@ -244,11 +253,6 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     if (pair >= pairs) return;
     const int h = pair % H;
     const int img = pair / H;
-    const int s = cu_seqlens[img];
-    const int n = cu_seqlens[img + 1] - s;
-    const int m0 = m_tile * kBM;
-    if (m0 >= n) return;                                       // whole group exits together
-
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = tid >> 6;
@@ -256,6 +260,58 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int g = lane >> 4;                                   // lane group
     const int64_t tok = (int64_t)H * kHeadDim;                 // elements between tokens
     const int64_t head_off = (int64_t)h * kHeadDim;
+    const int m0 = m_tile * kBM;
+
+    __shared__ uint16_t idx_lds[GATHER ? kMaxGatherTokens : 1];    // kept token positions, ascending
+    __shared__ int wave_cnt[WAVES];
+    int s, n;
+    if (GATHER) {
+        constexpr int kThreads = kWaveSize * WAVES;
+        constexpr int kPre = 4;                                // mask bytes per thread requested up front
+        const uint8_t* mask = keep + (int64_t)img * n_tok;
+        s = img * n_tok;
+        if (fill_mode == 1 && m_tile == 0) {                   // zero this head's slice of dropped rows
+            constexpr int kChunks = kHeadDim * (int)sizeof(OutT) / 16;
+            for (int t = tid / kChunks; t < n_tok; t += kThreads / kChunks)
+                if (mask[t] == 0)
+                    reinterpret_cast<uint4*>(o + (s + t) * tok + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
+        }
+        bool pre[kPre];
+#pragma unroll
+        for (int j = 0; j < kPre; ++j) {
+            const int t = j * kThreads + tid;
+            pre[j] = t < n_tok && mask[t] != 0;
+        }
+        n = 0;
+        auto append = [&](bool kept, int t) {                  // every thread of the group calls this
+            const uint64_t bits = __ballot(kept);
+            if (lane == 0) wave_cnt[wave] = __popcll(bits);
+            __syncthreads();
+            int before = n, total = 0;
+#pragma unroll
+            for (int w2 = 0; w2 < WAVES; ++w2) {
+                const int c = wave_cnt[w2];
+                before += w2 < wave ? c : 0;
+                total += c;
+            }
+            if (kept) idx_lds[before + __popcll(bits & ((1ull << lane) - 1ull))] = (uint16_t)t;
+            n += total;
+            __syncthreads();
+        };
+#pragma unroll
+        for (int j = 0; j < kPre; ++j)
+            if (j * kThreads < n_tok) append(pre[j], j * kThreads + tid);
+        for (int base = kPre * kThreads; base < n_tok; base += kThreads) {
+            const int t = base + tid;
+            append(t < n_tok && mask[t] != 0, t);
+        }
+    } else {
+        s = cu_seqlens[img];
+        n = cu_seqlens[img + 1] - s;
+    }
+    if (m0 >= n) return;                                       // whole group exits together
+    // row of the j-th token of this image in q / k / v / o
+    auto row_of = [&](int j) -> int64_t { return GATHER ? (int64_t)s + idx_lds[j] : (int64_t)s + j; };
     const bool wave_active = m0 + wave * 16 < n;               // wavefront has at least one real query
 
     // ---- tile-fill roles
@@ -270,9 +326,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int v_slot = (WAVES == 4) ? fill >> 3 : fill >> 4;   // 0..15
     const int v_kg = (v_slot & 8) | ((v_slot & 1) << 2) | ((v_slot >> 1) & 3);
     const int v_d0 = (WAVES == 4) ? 8 * (fill & 7) : 4 * (fill & 15);
-    const uint16_t* fill_src = fills_k ? k + (s + (fill >> 3)) * tok + head_off + 8 * (fill & 7)
-                                       : v + (s + 4 * v_kg) * tok + head_off + v_d0;
-    const int64_t fill_step = fills_k ? kKeyStep * tok : tok;  // elements between this thread's loads
+    const uint16_t* fill_src = fills_k ? k + head_off + 8 * (fill & 7) : v + head_off + v_d0;
     const int fill_key0 = fills_k ? (fill >> 3) : 4 * v_kg;
     const int fill_dkey = fills_k ? kKeyStep : 1;
     // V thread's 4 keys occupy 4 consecutive kappa slots
@@ -282,16 +336,17 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     uint4 raw[kLoads];
     auto prefetch = [&](int j0) {
         const int rem = n - j0;
-        const uint16_t* src = fill_src + (int64_t)j0 * tok;
 #pragma unroll
         for (int a = 0; a < kLoads; ++a) {
             raw[a] = make_uint4(0, 0, 0, 0);                   // keys past n are zero in LDS
             if (fills_k && a >= kKLoads) continue;
-            if (rem >= kBN || fill_key0 + fill_dkey * a < rem) {
+            const int key = fill_key0 + fill_dkey * a;         // key of the tile this load fetches
+            if (rem >= kBN || key < rem) {
+                const uint16_t* src = fill_src + row_of(j0 + key) * tok;
                 if (WAVES == 4 || fills_k) {
-                    raw[a] = *reinterpret_cast<const uint4*>(src + a * fill_step);
+                    raw[a] = *reinterpret_cast<const uint4*>(src);
                 } else {
-                    const uint2 two = *reinterpret_cast<const uint2*>(src + a * fill_step);
+                    const uint2 two = *reinterpret_cast<const uint2*>(src);
                     raw[a].x = two.x;
                     raw[a].y = two.y;
                 }
@@ -333,7 +388,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int q_row = m0 + wave * 16 + col;
     uint4 q_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
     if (q_row < n) {
-        const uint4* src = reinterpret_cast<const uint4*>(q + (s + q_row) * tok + head_off + 16 * g);
+        const uint4* src = reinterpret_cast<const uint4*>(q + row_of(q_row) * tok + head_off + 16 * g);
         q_raw[0] = src[0];
         q_raw[1] = src[1];
     }
@@ -384,15 +439,15 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) out16[4 * r + dt] = o_acc[dt][r] * inv;
-            store16(o + (s + q_row) * tok + head_off + 16 * g, out16);
+            store16(o + row_of(q_row) * tok + head_off + 16 * g, out16);
         }
     }
 }
 
-template <typename In, typename OutT>
+template <typename In, typename OutT, bool GATHER>
 hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
-                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
-                        hipStream_t stream) {
+                        const int32_t* cu_seqlens, const uint8_t* keep, int n_tok, int fill_mode,
+                        int B, int max_seqlen, int H, float scale, hipStream_t stream) {
     constexpr int kWaves = 4;                                  // 64 query rows per work-group
     constexpr int kGroup = 512;                                // pairs per dispatch batch
     const int q_tiles = (max_seqlen + 16 * kWaves - 1) / (16 * kWaves);
@@ -400,12 +455,27 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
     const int pairs8 = (pairs + kXcds - 1) / kXcds * kXcds;
     const int group = pairs8 < kGroup ? pairs8 : kGroup;
     const int batches = (pairs + group - 1) / group;
-    hipLaunchKernelGGL((attn_kernel<In, OutT, kWaves>), dim3(batches * q_tiles * group),
+    hipLaunchKernelGGL((attn_kernel<In, OutT, kWaves, GATHER>), dim3(batches * q_tiles * group),
                        dim3(kWaveSize * kWaves), 0, stream,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
-                       static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, H,
-                       pairs, q_tiles, group, fabsf(scale) * kLog2e, scale < 0.f ? 1 : 0);
+                       static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, keep, n_tok,
+                       fill_mode, H, pairs, q_tiles, group, fabsf(scale) * kLog2e, scale < 0.f ? 1 : 0);
     return hipGetLastError();
+}
+
+template <bool GATHER>
+hipError_t launch_any(const void* q, const void* k, const void* v, void* o, const int32_t* cu_seqlens,
+                      const uint8_t* keep, int n_tok, int fill_mode, int B, int max_seqlen, int H,
+                      float scale, ragged_dtype in_dt, ragged_dtype out_dt, hipStream_t stream) {
+    if (in_dt == RAGGED_F16 && out_dt == RAGGED_F16)
+        return launch_typed<F16, _Float16, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, scale, stream);
+    if (in_dt == RAGGED_F16 && out_dt == RAGGED_F32)
+        return launch_typed<F16, float, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, scale, stream);
+    if (in_dt == RAGGED_BF16 && out_dt == RAGGED_BF16)
+        return launch_typed<BF16, __bf16, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, scale, stream);
+    if (in_dt == RAGGED_BF16 && out_dt == RAGGED_F32)
+        return launch_typed<BF16, float, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, scale, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -413,15 +483,15 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
 hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
                        ragged_dtype in_dt, ragged_dtype out_dt, hipStream_t stream) {
-    if (in_dt == RAGGED_F16 && out_dt == RAGGED_F16)
-        return launch_typed<F16, _Float16>(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, stream);
-    if (in_dt == RAGGED_F16 && out_dt == RAGGED_F32)
-        return launch_typed<F16, float>(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, stream);
-    if (in_dt == RAGGED_BF16 && out_dt == RAGGED_BF16)
-        return launch_typed<BF16, __bf16>(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, stream);
-    if (in_dt == RAGGED_BF16 && out_dt == RAGGED_F32)
-        return launch_typed<BF16, float>(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, stream);
-    return hipErrorInvalidValue;
+    return launch_any<false>(q, k, v, o, cu_seqlens, nullptr, 0, 0, B, max_seqlen, H, scale, in_dt, out_dt, stream);
+}
+
+int attn_padded_max_tokens() { return kMaxGatherTokens; }
+
+hipError_t launch_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
+                              int B, int N, int H, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
+                              int fill_mode, hipStream_t stream) {
+    return launch_any<true>(q, k, v, o, nullptr, keep, N, fill_mode, B, N, H, scale, in_dt, out_dt, stream);
 }
 
 }  // namespace ragged

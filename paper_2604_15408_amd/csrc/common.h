@@ -23,6 +23,10 @@ hipError_t launch_unpack(const void* src, const uint8_t* keep, const int32_t* cu
 hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
                        ragged_dtype in_dt, ragged_dtype out_dt, hipStream_t stream);
+hipError_t launch_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
+                              int B, int N, int H, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
+                              int fill_mode, hipStream_t stream);
+int attn_padded_max_tokens();
 hipError_t launch_noop(int grid, hipStream_t stream);
 
 // Tokens of one image handled by one work-group of the pack / zero-filling unpack kernels.

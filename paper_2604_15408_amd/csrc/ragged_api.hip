@@ -7,7 +7,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 200;  // 0.2.0
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_BF16; }
@@ -47,6 +47,23 @@ int ragged_attn(const void* q, const void* k, const void* v, void* o,
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return RAGGED_ERR_UNSUPPORTED;
     return from_hip(ragged::launch_attn(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, in_dt, out_dt,
                                         static_cast<hipStream_t>(stream)));
+}
+
+int ragged_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
+                       int B, int N, int H, int D, float scale, ragged_dtype in_dt,
+                       ragged_dtype out_dt, int fill_mode, void* stream) {
+    if (!q || !k || !v || !o || !keep) return RAGGED_ERR_NULL;
+    if (B <= 0 || N <= 0 || H <= 0 || D <= 0 || !rows_fit(B, N)) return RAGGED_ERR_SHAPE;
+    const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)N + 63) / 64);
+    if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
+    if (D != 64 || N > ragged::attn_padded_max_tokens()) return RAGGED_ERR_UNSUPPORTED;
+    if (fill_mode != 0 && fill_mode != 1) return RAGGED_ERR_UNSUPPORTED;
+    const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
+                         (in_dt == RAGGED_BF16 && (out_dt == RAGGED_BF16 || out_dt == RAGGED_F32));
+    if (!pair_ok || !isfinite(scale)) return RAGGED_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_attn_padded(q, k, v, o, keep, B, N, H, scale, in_dt, out_dt, fill_mode,
+                                               static_cast<hipStream_t>(stream)));
 }
 
 int ragged_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlens,

@@ -133,6 +133,31 @@ def wall_steps(torch, fn, steps: int):
     return (time.perf_counter() - t0) / steps
 
 
+class PaddedPath:
+    """One attention layer on the padded layout: Q, K, V, O are [B, N, H, D] and the keep mask is
+    applied inside the single ragged_attn_padded launch."""
+
+    def __init__(self, w, fill_mode: int = 0):
+        import torch
+        from paper_2604_15408_amd import binding
+        self.torch, self.b, self.w, self.fill_mode = torch, binding, w, fill_mode
+        dev = "cuda:0"
+        g = torch.Generator().manual_seed(w.seed * 7919 + 3)
+        tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
+        self.q, self.k, self.v = (torch.randn(w.B, w.N, w.H, w.D, generator=g, dtype=torch.float32)
+                                  .to(tdt).to(dev) for _ in range(3))
+        self.o = torch.zeros_like(self.q)
+        self.keep = w.keep.to(dev)
+        torch.cuda.synchronize()
+
+    def run(self):
+        self.b.ragged_attn_padded(self.q, self.k, self.v, self.o, self.keep, self.w.scale, self.fill_mode)
+
+    def prepared(self):
+        return self.b.prepare_attn_padded(self.q, self.k, self.v, self.o, self.keep, self.w.scale,
+                                          self.fill_mode)
+
+
 class Pipeline:
     """The 12-layer progressive-pruning loop (B=64, N=197, C=768): per layer
     pack(X_l, mask_l) -> ragged_attn(Q_l, K_l, V_l; cu_seqlens from pack) -> unpack(O_l) -> X_{l+1}.

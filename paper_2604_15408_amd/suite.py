@@ -17,7 +17,7 @@ import os
 import sys
 
 from . import workloads as wl
-from .harness import REPLICAS, Path, Pipeline, capture, event_time_us, wall_steps
+from .harness import REPLICAS, PaddedPath, Path, Pipeline, capture, event_time_us, wall_steps
 
 
 def stage_times(torch, p: Path):
@@ -36,7 +36,11 @@ def case(torch, w, label: str):
     step_graph = wall_steps(torch, g.replay, 300) * 1e6
     lean = p.prepared_step()
     step_lean = wall_steps(torch, lean, 300) * 1e6
-    return {"case": label, "workload": w.name, "dtype": w.dtype, "B": w.B, "N": w.N, "T": w.T,
+    fused = PaddedPath(w, 0)
+    g_fused = capture(torch, fused.run, REPLICAS)
+    fused_us = event_time_us(torch, g_fused.replay, iters=30)[0] / REPLICAS
+    fused_wall = wall_steps(torch, fused.prepared(), 300) * 1e6
+    return {"case": label, "workload": w.name, "fused_single_launch_us": {"kernel": fused_us, "wall_prepared": fused_wall}, "dtype": w.dtype, "B": w.B, "N": w.N, "T": w.T,
             "max_len": max(w.lengths), "kernel_us": us,
             "gbs": {k: alg[k]["bytes"] / (us[k] * 1e-6) / 1e9 for k in us},
             "attn_tflops": alg["attn"]["flops"] / (us["attn"] * 1e-6) / 1e12,

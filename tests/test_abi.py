@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() >= 100
+    assert binding.version() >= 200
     assert binding.status_string(0) == "ok"
     texts = {binding.status_string(s) for s in range(6)}
     assert len(texts) == 6 and binding.status_string(99) == "unknown"
@@ -81,6 +81,17 @@ def test_unpack_validation(lib):
         assert _unpack(lib, **bad) == 2
     for bad in (dict(dt=2), dict(C=20), dict(src=FAKE + 1), dict(out=FAKE + 2)):
         assert _unpack(lib, **bad) == 3
+
+
+def test_attn_padded_validation(lib):
+    def call(q=FAKE, k=FAKE, v=FAKE, o=FAKE, keep=FAKE, B=2, N=8, H=2, D=64, scale=0.125, i=0, od=0, fm=0):
+        return lib.ragged_attn_padded(q, k, v, o, keep, B, N, H, D, scale, i, od, fm, None)
+    for null in ("q", "k", "v", "o", "keep"):
+        assert call(**{null: None}) == 1
+    for bad in (dict(B=0), dict(N=0), dict(H=-1), dict(D=0), dict(B=1 << 20, N=1 << 20)):
+        assert call(**bad) == 2
+    for bad in (dict(D=32), dict(N=1537), dict(fm=2), dict(i=1, od=0), dict(scale=float("nan")), dict(v=FAKE + 8)):
+        assert call(**bad) == 3
 
 
 def test_noop_validation(lib):
