@@ -56,6 +56,10 @@ def _load():
         lib.oracle_attn_row.restype = i32
         lib.oracle_attn_padded.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, ctypes.c_float, vp]
         lib.oracle_attn_padded.restype = i32
+        lib.oracle_repack.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+        lib.oracle_repack.restype = i64
+        lib.oracle_cls_extract.argtypes = [vp, vp, i32, i32, vp]
+        lib.oracle_cls_extract.restype = None
         lib.oracle_max_threads.argtypes = []
         lib.oracle_max_threads.restype = i32
         _lib = lib
@@ -187,4 +191,32 @@ def attn_padded(q, k, v, keep, scale: float, dtype: str = "f16") -> np.ndarray:
                                     float(scale), _ptr(out))
     if rc != 0:
         raise MemoryError("oracle_attn_padded failed to allocate scratch")
+    return out
+
+
+def repack(packed_words, keep_rows, cu_seqlens):
+    """packed [T,C] words, keep_rows [>=T] bytes, cu [B+1] -> (packed_out [T',C], cu_out [B+1], gather_out [T'])."""
+    src = _words(packed_words, 2)
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    T, C = src.shape
+    if int(cu[-1]) != T:
+        raise ValueError("cu_seqlens[-1] must equal the number of packed rows")
+    kr = np.ascontiguousarray(keep_rows)
+    if kr.dtype == np.bool_:
+        kr = kr.view(np.uint8)
+    if kr.dtype != np.uint8 or kr.ndim != 1 or kr.size < T:
+        raise TypeError("keep_rows must be a uint8/bool vector with at least T entries")
+    out = np.zeros((max(T, 1), C), dtype=np.uint16)
+    cu_out = np.zeros(cu.size, dtype=np.int32)
+    gidx = np.zeros(max(T, 1), dtype=np.int32)
+    T2 = int(_load().oracle_repack(_ptr(src), _ptr(kr), _ptr(cu), cu.size - 1, C, _ptr(out), _ptr(cu_out), _ptr(gidx)))
+    return out[:T2].copy(), cu_out, gidx[:T2].copy()
+
+
+def cls_extract(packed_words, cu_seqlens) -> np.ndarray:
+    """First packed row of every image ([B,C] words; +0 for an image with no rows)."""
+    src = _words(packed_words, 2)
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    out = np.full((cu.size - 1, src.shape[1]), 0xFFFF, dtype=np.uint16)
+    _load().oracle_cls_extract(_ptr(src), _ptr(cu), cu.size - 1, src.shape[1], _ptr(out))
     return out

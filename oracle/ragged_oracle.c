@@ -301,6 +301,45 @@ int oracle_attn_padded(const uint16_t *q, const uint16_t *k, const uint16_t *v, 
     return 0;
 }
 
+/*
+ * Re-pack: apply a second keep decision to an ALREADY packed buffer (progressive pruning while
+ * staying packed, as in the pipeline of Section 4.3 where the buffer is packed once and later
+ * layers keep working on it).  keep_rows has one byte per packed row (only rows < cu_in[B] count).
+ * Kept rows are appended in ascending row order; cu_out[i] = kept rows before cu_in[i];
+ * gather_out[r'] = the input row that became output row r'.  Returns the new total.
+ */
+int64_t oracle_repack(const uint16_t *packed_in, const uint8_t *keep_rows, const int32_t *cu_in,
+                      int B, int C, uint16_t *packed_out, int32_t *cu_out, int32_t *gather_out)
+{
+    int64_t next = 0;
+    cu_out[0] = 0;
+    for (int i = 0; i < B; ++i) {
+        for (int64_t r = cu_in[i]; r < cu_in[i + 1]; ++r) {
+            if (keep_rows[r] != 0) {
+                gather_out[next] = (int32_t)r;
+                memcpy(packed_out + next * C, packed_in + r * C, (size_t)C * sizeof(uint16_t));
+                ++next;
+            }
+        }
+        cu_out[i + 1] = (int32_t)next;
+    }
+    return next;
+}
+
+/*
+ * CLS extraction (Section 4.3, step 5: the class token is read from the packed buffer): the first
+ * packed row of every image; an image with no rows yields +0 words.
+ */
+void oracle_cls_extract(const uint16_t *packed, const int32_t *cu_seqlens, int B, int C, uint16_t *out)
+{
+    for (int i = 0; i < B; ++i) {
+        if (cu_seqlens[i + 1] > cu_seqlens[i])
+            memcpy(out + (int64_t)i * C, packed + (int64_t)cu_seqlens[i] * C, (size_t)C * sizeof(uint16_t));
+        else
+            memset(out + (int64_t)i * C, 0, (size_t)C * sizeof(uint16_t));
+    }
+}
+
 /* Number of OpenMP threads a parallel region would get by default (1 without OpenMP). */
 int oracle_max_threads(void)
 {

@@ -102,3 +102,55 @@ def test_workload_generators_are_seeded_and_shaped():
     assert int(masks[2].sum()) < int(masks[1].sum()) and bool(masks[-1][:, 0].all())
     assert [w.dtype for w in wl.sweep()] == ["bf16"] * 6
     assert wl.sweep()[0].T == 32 * 197
+
+
+# ---- staying packed: re-pack and CLS extraction ---------------------------------------------------
+
+def test_repack_equals_numpy_indexing_and_boundary_counts():
+    x, keep = _case(5, 29, 8, 0.6, 20)
+    keep[2, :] = 0                                            # an empty image in the middle
+    packed, cu, _ = oracle.pack(x, keep)
+    T = packed.shape[0]
+    rows = (np.random.default_rng(3).random(T + 5) < 0.5).astype(np.uint8)   # extra bytes past T are ignored
+    out, cu2, g2 = oracle.repack(packed, rows, cu)
+    sel = rows[:T].astype(bool)
+    assert np.array_equal(out, packed[sel])
+    assert np.array_equal(g2, np.flatnonzero(sel))
+    csum = np.concatenate([[0], np.cumsum(sel)])
+    assert np.array_equal(cu2, csum[cu])
+
+
+def test_repack_of_pack_equals_pack_with_both_masks():
+    """Pruning an already packed buffer must give what packing with the combined mask gives."""
+    x, keep1 = _case(4, 41, 16, 0.7, 21)
+    keep2 = wl.keep_bernoulli(4, 41, 0.5, 22).numpy()
+    packed1, cu1, _ = oracle.pack(x, keep1)
+    rows = keep2[keep1.astype(bool)]                           # second decision, per surviving token
+    out, cu2, g2 = oracle.repack(packed1, rows, cu1)
+    want_packed, want_cu, want_gidx = oracle.pack(x, keep1 & keep2)
+    assert np.array_equal(out, want_packed) and np.array_equal(cu2, want_cu)
+    _, _, gidx1 = oracle.pack(x, keep1)
+    assert np.array_equal(gidx1[g2], want_gidx)                # composing the two gather maps
+
+
+def test_repack_keep_all_and_keep_none():
+    x, keep = _case(3, 17, 8, 0.5, 23)
+    packed, cu, _ = oracle.pack(x, keep)
+    T = packed.shape[0]
+    out, cu2, g2 = oracle.repack(packed, np.ones(T, np.uint8), cu)
+    assert np.array_equal(out, packed) and np.array_equal(cu2, cu) and np.array_equal(g2, np.arange(T))
+    out, cu2, g2 = oracle.repack(packed, np.zeros(T, np.uint8), cu)
+    assert out.shape == (0, 8) and not cu2.any() and g2.size == 0
+
+
+def test_cls_extract_is_first_row_of_each_image():
+    x, keep = _case(5, 23, 8, 0.4, 24)
+    keep[:, 0] = 1
+    keep[3, :] = 0                                            # image 3 has no rows at all
+    packed, cu, _ = oracle.pack(x, keep)
+    cls = oracle.cls_extract(packed, cu)
+    for i in range(5):
+        if i == 3:
+            assert not cls[i].any()
+        else:
+            assert np.array_equal(cls[i], x[i, 0])             # CLS is token 0 and always kept
