@@ -33,9 +33,10 @@ extern "C" {
 typedef enum {
     RAGGED_OK = 0,
     RAGGED_ERR_NULL = 1,         /* a required pointer is NULL                                   */
-    RAGGED_ERR_SHAPE = 2,        /* a dimension is <= 0, overflows int32 row indexing, or C != H*D */
+    RAGGED_ERR_SHAPE = 2,        /* a dimension is <= 0, overflows int32 row indexing, or a token
+                                    stride is shorter than a row                                  */
     RAGGED_ERR_UNSUPPORTED = 3,  /* dtype pair, head dim, alignment or fill mode not supported    */
-    RAGGED_ERR_CAPACITY = 4,     /* cap_rows < 1                                                  */
+    RAGGED_ERR_CAPACITY = 4,     /* a row capacity (cap_rows, cap_in, cap_out) is < 1             */
     RAGGED_ERR_HIP = 5           /* the HIP runtime refused the launch                            */
 } ragged_status;
 
@@ -87,6 +88,25 @@ int ragged_attn(const void* q, const void* k, const void* v, void* o,
                 float scale, ragged_dtype in_dt, ragged_dtype out_dt, void* stream);
 
 /*
+ * ragged_attn_strided -- ragged_attn on token rows that are not contiguous: token t of q, k, v
+ * starts in_tok_stride elements after token t-1, token t of o out_tok_stride elements after its
+ * predecessor; inside a token the layout stays [H, D].  This is what the late layers of Section 4.3
+ * ("End-to-End Pipeline Integration", step 4: attention and MLP run on the packed buffer) need
+ * between their linear layers: the QKV projection of packed rows writes one [T, 3, H, D] buffer, and
+ * q = base, k = base + H*D, v = base + 2*H*D with in_tok_stride = 3*H*D attends on it in place,
+ * without three de-interleaving copies.  ragged_attn is this call with both strides = H*D.
+ *
+ * Strides are in elements of the respective dtype, must be >= H*D, and every token row must start
+ * on a 16-byte boundary (in_tok_stride a multiple of 8; out_tok_stride a multiple of 8 for 16-bit
+ * outputs, of 4 for F32).  Everything else as for ragged_attn; outputs are bit-identical to
+ * ragged_attn on contiguous copies of the same rows.
+ */
+int ragged_attn_strided(const void* q, const void* k, const void* v, void* o,
+                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
+                        int64_t in_tok_stride, int64_t out_tok_stride, float scale,
+                        ragged_dtype in_dt, ragged_dtype out_dt, void* stream);
+
+/*
  * ragged_unpack -- the inverse scatter of ragged_pack (the paper names the stage in its
  * "pack-attend-unpack pipeline", Sections 1 and 4, without describing it).
  *
@@ -122,6 +142,40 @@ int ragged_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlen
 int ragged_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
                        int B, int N, int H, int D, float scale, ragged_dtype in_dt,
                        ragged_dtype out_dt, int fill_mode, void* stream);
+
+/*
+ * ragged_repack -- a second pruning decision applied to rows that are ALREADY packed.  Section 4.3
+ * packs once and keeps every later layer on the packed buffer; pruning methods that drop tokens
+ * at several depths (Section 2, "Token Pruning for ViTs": DynamicViT and EViT prune progressively)
+ * then need a keep mask applied to packed rows, instead of an unpack -> pack round trip through
+ * the padded tensor.  Equivalent to ragged_pack with the AND of both masks, in one launch:
+ *
+ *   packed_in  [cap_in, C]  packed rows; rows [0, T_in) are valid, T_in = cu_in[B] <= cap_in
+ *   keep_rows  [cap_in]     one byte per packed row, nonzero = keep; bytes at rows >= T_in are ignored
+ *   cu_in      [B + 1]      boundaries of packed_in
+ *   packed_out [cap_out, C] out: kept rows in the same order
+ *   cu_out     [B + 1]      out: cu_out[i] = number of kept rows before row cu_in[i]
+ *   gather_out [cap_out]    out: gather_out[r] = row of packed_in that packed_out row r came from
+ *                           (compose with the first gather_idx to get back to the padded tensor)
+ *
+ * Rows whose destination would be >= cap_out are not written (cu_out still holds the true counts).
+ * packed_out must not overlap packed_in; cu_out must not alias cu_in.
+ */
+int ragged_repack(const void* packed_in, const uint8_t* keep_rows, const int32_t* cu_in, int B,
+                  int64_t cap_in, int C, ragged_dtype dt, void* packed_out, int64_t cap_out,
+                  int32_t* cu_out, int32_t* gather_out, void* stream);
+
+/*
+ * ragged_cls_extract -- step 5 of Section 4.3: the classifier reads each image's class token from
+ * the packed buffer.  Packing keeps token order (Section 4.1), so a class token at position 0 that
+ * the keep mask retains is the image's first packed row.
+ *
+ *   packed     [T, C]   packed rows
+ *   cu_seqlens [B + 1]
+ *   out        [B, C]   out: out[i, :] = packed[cu_seqlens[i], :]; +0 words for an image with no rows
+ */
+int ragged_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int C, ragged_dtype dt,
+                       void* out, void* stream);
 
 /*
  * ragged_noop -- enqueue an empty kernel of `grid` work-groups of 256 threads on `stream`.

@@ -19,8 +19,8 @@ RAGGED_OK = 0
 RAGGED_F16, RAGGED_BF16, RAGGED_F32 = 0, 1, 2
 _DTYPE_CODE = {torch.float16: RAGGED_F16, torch.bfloat16: RAGGED_BF16, torch.float32: RAGGED_F32}
 
-EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_padded", "ragged_unpack", "ragged_noop",
-           "ragged_status_string", "ragged_version")
+EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_strided", "ragged_attn_padded", "ragged_unpack",
+           "ragged_repack", "ragged_cls_extract", "ragged_noop", "ragged_status_string", "ragged_version")
 
 _lib = None
 
@@ -45,6 +45,12 @@ def load() -> ctypes.CDLL:
         lib.ragged_pack.restype = i32
         lib.ragged_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, vp]
         lib.ragged_attn.restype = i32
+        lib.ragged_attn_strided.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, f32, i32, i32, vp]
+        lib.ragged_attn_strided.restype = i32
+        lib.ragged_repack.argtypes = [vp, vp, vp, i32, i64, i32, i32, vp, i64, vp, vp, vp]
+        lib.ragged_repack.restype = i32
+        lib.ragged_cls_extract.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+        lib.ragged_cls_extract.restype = i32
         lib.ragged_attn_padded.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, i32, vp]
         lib.ragged_attn_padded.restype = i32
         lib.ragged_unpack.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
@@ -117,6 +123,72 @@ def ragged_attn(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=No
     _check("ragged_attn", st)
 
 
+def _token_rows(t: torch.Tensor, name: str, dtype, shape):
+    """(pointer, token stride) of a [rows, H, D] view whose tokens are a constant number of elements
+    apart and whose [H, D] block is contiguous inside a token (e.g. ``qkv[:, 0]`` of [rows, 3, H, D])."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor")
+    if t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise TypeError(f"{name} has dtype {t.dtype}, expected {dtype}")
+    if t.dim() != 3 or (shape is not None and tuple(t.shape) != tuple(shape)):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected [rows, H, D]")
+    rows, H, D = t.shape
+    if t.stride(2) != 1 or t.stride(1) != D:
+        raise ValueError(f"{name}: the [H, D] block of a token must be contiguous")
+    return t.data_ptr(), (t.stride(0) if rows > 1 else max(t.stride(0), H * D))
+
+
+def _attn_strided_args(q, k, v, o, cu_seqlens, max_seqlen, scale, stream):
+    rows, H, D = q.shape
+    B = cu_seqlens.shape[0] - 1
+    (qp, qs), (kp, ks), (vp, vs) = (_token_rows(t, n, (torch.float16, torch.bfloat16), q.shape)
+                                    for t, n in ((q, "q"), (k, "k"), (v, "v")))
+    if not (k.dtype == v.dtype == q.dtype) or not (qs == ks == vs):
+        raise ValueError("q, k, v must share dtype and token stride")
+    op, os_ = _token_rows(o, "o", (q.dtype, torch.float32), q.shape)
+    return (qp, kp, vp, op, _dev(cu_seqlens, "cu_seqlens", torch.int32), B, int(max_seqlen), H, D,
+            int(qs), int(os_), float(scale), _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], _stream(stream))
+
+
+def ragged_attn_strided(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=None) -> None:
+    """ragged_attn on [rows,H,D] views with a token stride, e.g. the three slices of a fused
+    [rows,3,H,D] QKV buffer; o may be a strided view too."""
+    _check("ragged_attn_strided",
+           load().ragged_attn_strided(*_attn_strided_args(q, k, v, o, cu_seqlens, max_seqlen, scale, stream)))
+
+
+def _repack_args(packed_in, keep_rows, cu_in, packed_out, cu_out, gather_out, stream):
+    cap_in, C = packed_in.shape
+    cap_out = packed_out.shape[0]
+    B = cu_in.shape[0] - 1
+    return (_dev(packed_in, "packed_in", (torch.float16, torch.bfloat16)),
+            _dev(keep_rows, "keep_rows", (torch.uint8, torch.bool), (cap_in,)),
+            _dev(cu_in, "cu_in", torch.int32), B, cap_in, C, _DTYPE_CODE[packed_in.dtype],
+            _dev(packed_out, "packed_out", packed_in.dtype, (cap_out, C)), cap_out,
+            _dev(cu_out, "cu_out", torch.int32, (B + 1,)),
+            _dev(gather_out, "gather_out", torch.int32, (cap_out,)), _stream(stream))
+
+
+def ragged_repack(packed_in, keep_rows, cu_in, packed_out, cu_out, gather_out, stream=None) -> None:
+    """packed_in [cap_in,C], keep_rows [cap_in], cu_in [B+1] -> packed_out [cap_out,C], cu_out [B+1],
+    gather_out [cap_out]: a second keep decision on packed rows."""
+    _check("ragged_repack",
+           load().ragged_repack(*_repack_args(packed_in, keep_rows, cu_in, packed_out, cu_out, gather_out, stream)))
+
+
+def _cls_args(packed, cu_seqlens, out, stream):
+    B = cu_seqlens.shape[0] - 1
+    C = packed.shape[1]
+    return (_dev(packed, "packed", (torch.float16, torch.bfloat16)),
+            _dev(cu_seqlens, "cu_seqlens", torch.int32), B, C, _DTYPE_CODE[packed.dtype],
+            _dev(out, "out", packed.dtype, (B, C)), _stream(stream))
+
+
+def ragged_cls_extract(packed, cu_seqlens, out, stream=None) -> None:
+    """out[i] = packed[cu_seqlens[i]] (first kept row of image i; zeros if the image has none)."""
+    _check("ragged_cls_extract", load().ragged_cls_extract(*_cls_args(packed, cu_seqlens, out, stream)))
+
+
 def _attn_padded_args(q, k, v, o, keep, scale, fill_mode, stream):
     B, N, H, D = q.shape
     return (_dev(q, "q", (torch.float16, torch.bfloat16)), _dev(k, "k", q.dtype, q.shape),
@@ -181,6 +253,22 @@ def prepare_attn(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=N
             _dev(cu_seqlens, "cu_seqlens", torch.int32), B, int(max_seqlen), H, D, float(scale),
             _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], _stream(stream))
     return Prepared("ragged_attn", load().ragged_attn, args, (q, k, v, o, cu_seqlens))
+
+
+def prepare_attn_strided(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=None) -> Prepared:
+    return Prepared("ragged_attn_strided", load().ragged_attn_strided,
+                    _attn_strided_args(q, k, v, o, cu_seqlens, max_seqlen, scale, stream), (q, k, v, o, cu_seqlens))
+
+
+def prepare_repack(packed_in, keep_rows, cu_in, packed_out, cu_out, gather_out, stream=None) -> Prepared:
+    return Prepared("ragged_repack", load().ragged_repack,
+                    _repack_args(packed_in, keep_rows, cu_in, packed_out, cu_out, gather_out, stream),
+                    (packed_in, keep_rows, cu_in, packed_out, cu_out, gather_out))
+
+
+def prepare_cls_extract(packed, cu_seqlens, out, stream=None) -> Prepared:
+    return Prepared("ragged_cls_extract", load().ragged_cls_extract, _cls_args(packed, cu_seqlens, out, stream),
+                    (packed, cu_seqlens, out))
 
 
 def prepare_attn_padded(q, k, v, o, keep, scale: float, fill_mode: int = 0, stream=None) -> Prepared:

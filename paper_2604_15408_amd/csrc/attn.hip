@@ -234,7 +234,7 @@ __global__ __launch_bounds__(kWaveSize * WAVES, 4)
 void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                  const uint16_t* __restrict__ v, OutT* __restrict__ o,
                  const int32_t* __restrict__ cu_seqlens, const uint8_t* __restrict__ keep, int n_tok,
-                 int fill_mode, int H, int pairs, int q_tiles, int group,
+                 int fill_mode, int H, int64_t tok, int64_t tok_o, int pairs, int q_tiles, int group,
                  float scale_log2e, int negate_q) {
     typedef typename In::vec8 vec8;
     constexpr int kBM = 16 * WAVES;                            // queries per work-group
@@ -258,7 +258,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int wave = tid >> 6;
     const int col = lane & 15;                                 // query inside the wavefront's 16
     const int g = lane >> 4;                                   // lane group
-    const int64_t tok = (int64_t)H * kHeadDim;                 // elements between tokens
+    // tok / tok_o: elements between consecutive tokens of q, k, v / of o (H*64 when contiguous)
     const int64_t head_off = (int64_t)h * kHeadDim;
     const int m0 = m_tile * kBM;
 
@@ -274,7 +274,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             constexpr int kChunks = kHeadDim * (int)sizeof(OutT) / 16;
             for (int t = tid / kChunks; t < n_tok; t += kThreads / kChunks)
                 if (mask[t] == 0)
-                    reinterpret_cast<uint4*>(o + (s + t) * tok + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
+                    reinterpret_cast<uint4*>(o + (s + t) * tok_o + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
         }
         bool pre[kPre];
 #pragma unroll
@@ -439,7 +439,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) out16[4 * r + dt] = o_acc[dt][r] * inv;
-            store16(o + row_of(q_row) * tok + head_off + 16 * g, out16);
+            store16(o + row_of(q_row) * tok_o + head_off + 16 * g, out16);
         }
     }
 }
@@ -447,7 +447,8 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 template <typename In, typename OutT, bool GATHER>
 hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
                         const int32_t* cu_seqlens, const uint8_t* keep, int n_tok, int fill_mode,
-                        int B, int max_seqlen, int H, float scale, hipStream_t stream) {
+                        int B, int max_seqlen, int H, int64_t in_tok, int64_t out_tok, float scale,
+                        hipStream_t stream) {
     constexpr int kWaves = 4;                                  // 64 query rows per work-group
     constexpr int kGroup = 512;                                // pairs per dispatch batch
     const int q_tiles = (max_seqlen + 16 * kWaves - 1) / (16 * kWaves);
@@ -459,31 +460,35 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
                        dim3(kWaveSize * kWaves), 0, stream,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                        static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, keep, n_tok,
-                       fill_mode, H, pairs, q_tiles, group, fabsf(scale) * kLog2e, scale < 0.f ? 1 : 0);
+                       fill_mode, H, in_tok, out_tok, pairs, q_tiles, group, fabsf(scale) * kLog2e,
+                       scale < 0.f ? 1 : 0);
     return hipGetLastError();
 }
 
 template <bool GATHER>
 hipError_t launch_any(const void* q, const void* k, const void* v, void* o, const int32_t* cu_seqlens,
                       const uint8_t* keep, int n_tok, int fill_mode, int B, int max_seqlen, int H,
-                      float scale, ragged_dtype in_dt, ragged_dtype out_dt, hipStream_t stream) {
+                      int64_t in_tok, int64_t out_tok, float scale, ragged_dtype in_dt,
+                      ragged_dtype out_dt, hipStream_t stream) {
     if (in_dt == RAGGED_F16 && out_dt == RAGGED_F16)
-        return launch_typed<F16, _Float16, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, scale, stream);
+        return launch_typed<F16, _Float16, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, stream);
     if (in_dt == RAGGED_F16 && out_dt == RAGGED_F32)
-        return launch_typed<F16, float, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, scale, stream);
+        return launch_typed<F16, float, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, stream);
     if (in_dt == RAGGED_BF16 && out_dt == RAGGED_BF16)
-        return launch_typed<BF16, __bf16, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, scale, stream);
+        return launch_typed<BF16, __bf16, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, stream);
     if (in_dt == RAGGED_BF16 && out_dt == RAGGED_F32)
-        return launch_typed<BF16, float, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, scale, stream);
+        return launch_typed<BF16, float, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, stream);
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
 hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
-                       const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
-                       ragged_dtype in_dt, ragged_dtype out_dt, hipStream_t stream) {
-    return launch_any<false>(q, k, v, o, cu_seqlens, nullptr, 0, 0, B, max_seqlen, H, scale, in_dt, out_dt, stream);
+                       const int32_t* cu_seqlens, int B, int max_seqlen, int H, int64_t in_tok,
+                       int64_t out_tok, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
+                       hipStream_t stream) {
+    return launch_any<false>(q, k, v, o, cu_seqlens, nullptr, 0, 0, B, max_seqlen, H, in_tok, out_tok, scale,
+                             in_dt, out_dt, stream);
 }
 
 int attn_padded_max_tokens() { return kMaxGatherTokens; }
@@ -491,7 +496,9 @@ int attn_padded_max_tokens() { return kMaxGatherTokens; }
 hipError_t launch_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
                               int B, int N, int H, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
                               int fill_mode, hipStream_t stream) {
-    return launch_any<true>(q, k, v, o, nullptr, keep, N, fill_mode, B, N, H, scale, in_dt, out_dt, stream);
+    const int64_t tok = (int64_t)H * kHeadDim;
+    return launch_any<true>(q, k, v, o, nullptr, keep, N, fill_mode, B, N, H, tok, tok, scale, in_dt, out_dt,
+                            stream);
 }
 
 }  // namespace ragged

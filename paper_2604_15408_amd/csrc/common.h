@@ -20,12 +20,19 @@ hipError_t launch_pack(const void* x, const uint8_t* keep, int B, int N, int C, 
 hipError_t launch_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlens,
                          const int32_t* gather_idx, int B, int N, int C, void* out, int fill_mode,
                          hipStream_t stream);
+// in_tok / out_tok: elements between consecutive tokens of q, k, v / of o
 hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
-                       const int32_t* cu_seqlens, int B, int max_seqlen, int H, float scale,
-                       ragged_dtype in_dt, ragged_dtype out_dt, hipStream_t stream);
+                       const int32_t* cu_seqlens, int B, int max_seqlen, int H, int64_t in_tok,
+                       int64_t out_tok, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
+                       hipStream_t stream);
 hipError_t launch_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
                               int B, int N, int H, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
                               int fill_mode, hipStream_t stream);
+hipError_t launch_repack(const void* packed_in, const uint8_t* keep_rows, const int32_t* cu_in, int B,
+                         int64_t cap_in, int C, void* packed_out, int64_t cap_out, int32_t* cu_out,
+                         int32_t* gather_out, hipStream_t stream);
+hipError_t launch_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int C, void* out,
+                              hipStream_t stream);
 int attn_padded_max_tokens();
 hipError_t launch_noop(int grid, hipStream_t stream);
 

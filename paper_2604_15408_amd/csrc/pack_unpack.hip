@@ -256,6 +256,68 @@ void unpack_fill_kernel(const uint4* __restrict__ src, const uint8_t* __restrict
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// re-pack: a second keep decision on an already packed buffer.  One work-group per chunk of <= 64
+// consecutive packed rows; the structure is that of pack with the flat row index in place of
+// (image, token).  cu_out[i] = kept rows before row cu_in[i]: written by the group whose chunk
+// contains that row index (the group starting at or just below T_in also runs, for boundaries that
+// equal T_in).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlockThreads)
+void repack_kernel(const uint4* __restrict__ packed_in, const uint8_t* __restrict__ keep_rows,
+                   const int32_t* __restrict__ cu_in, int B, int64_t cap_in, int units,
+                   uint4* __restrict__ packed_out, int64_t cap_out, int32_t* __restrict__ cu_out,
+                   int32_t* __restrict__ gather_out, int chunk) {
+    __shared__ int lds4[4];
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int64_t r0 = (int64_t)blockIdx.x * chunk;            // <= cap_in by the grid size
+    const int t_in = cu_in[B];
+    // requested before t_in is known: both ranges lie inside the cap_in bytes of keep_rows
+    const bool in_cap = lane < chunk && r0 + lane < cap_in;
+    const uint8_t my_keep = in_cap ? keep_rows[r0 + lane] : (uint8_t)0;
+    const PrefixLoads prefix = prefix_issue(keep_rows, (int)r0);
+    if (r0 > t_in) return;                                     // whole group; rows >= t_in do not exist
+
+    const bool mine = my_keep != 0 && r0 + lane < t_in;
+    const uint64_t bits = __ballot(mine);
+    const int P = prefix_finish(keep_rows, prefix, lds4);      // kept rows before this chunk
+
+    if (wave == 0 && mine) {
+        const int64_t dst = (int64_t)P + __popcll(bits & ((1ull << lane) - 1ull));
+        if (dst < cap_out) gather_out[dst] = (int32_t)(r0 + lane);
+    }
+    for (int i = threadIdx.x; i <= B; i += kBlockThreads) {
+        const int64_t c = cu_in[i];
+        if (c >= r0 && c < r0 + chunk) cu_out[i] = P + __popcll(bits & ((1ull << (int)(c - r0)) - 1ull));
+    }
+    uint64_t rest = bits;
+    for (int k = 0; rest != 0; ++k) {
+        const int t = __builtin_ctzll(rest);
+        rest &= rest - 1;
+        if ((k & 3) != wave) continue;
+        const int64_t dst = (int64_t)P + k;
+        if (dst >= cap_out) break;
+        wave_copy_row(packed_in + (r0 + t) * units, packed_out + dst * units, units, lane);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// CLS extraction: one wavefront per image copies the image's first packed row (zeros if it has none).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlockThreads)
+void cls_extract_kernel(const uint4* __restrict__ packed, const int32_t* __restrict__ cu_seqlens, int B,
+                        int units, uint4* __restrict__ out) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int i = blockIdx.x * (kBlockThreads / kWaveSize) + (threadIdx.x >> 6);
+    if (i >= B) return;
+    const int s = cu_seqlens[i];
+    const bool has = cu_seqlens[i + 1] > s;
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    for (int u = lane; u < units; u += kWaveSize)
+        out[(int64_t)i * units + u] = has ? packed[(int64_t)s * units + u] : zero;
+}
+
 __global__ void noop_kernel() {}
 
 }  // namespace
@@ -290,6 +352,26 @@ hipError_t launch_unpack(const void* src, const uint8_t* keep, const int32_t* cu
                            static_cast<const uint4*>(src), keep, cu_seqlens, N, C / 8,
                            static_cast<uint4*>(out), chunk, cpi);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_repack(const void* packed_in, const uint8_t* keep_rows, const int32_t* cu_in, int B,
+                         int64_t cap_in, int C, void* packed_out, int64_t cap_out, int32_t* cu_out,
+                         int32_t* gather_out, hipStream_t stream) {
+    int chunk = 8;
+    while (chunk < 64 && cap_in / chunk > 4096) chunk *= 2;
+    const int grid = (int)(cap_in / chunk) + 1;                // covers every chunk start <= cap_in
+    hipLaunchKernelGGL(repack_kernel, dim3(grid), dim3(kBlockThreads), 0, stream,
+                       static_cast<const uint4*>(packed_in), keep_rows, cu_in, B, cap_in, C / 8,
+                       static_cast<uint4*>(packed_out), cap_out, cu_out, gather_out, chunk);
+    return hipGetLastError();
+}
+
+hipError_t launch_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int C, void* out,
+                              hipStream_t stream) {
+    const int per = kBlockThreads / kWaveSize;
+    hipLaunchKernelGGL(cls_extract_kernel, dim3((B + per - 1) / per), dim3(kBlockThreads), 0, stream,
+                       static_cast<const uint4*>(packed), cu_seqlens, B, C / 8, static_cast<uint4*>(out));
     return hipGetLastError();
 }
 

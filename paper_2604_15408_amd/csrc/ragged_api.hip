@@ -7,7 +7,7 @@
 
 namespace {
 
-constexpr int kVersion = 200;  // 0.2.0
+constexpr int kVersion = 300;  // 0.3.0
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_BF16; }
@@ -32,21 +32,36 @@ int ragged_pack(const void* x, const uint8_t* keep, int B, int N, int C, ragged_
                                         static_cast<hipStream_t>(stream)));
 }
 
-int ragged_attn(const void* q, const void* k, const void* v, void* o,
-                const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
-                float scale, ragged_dtype in_dt, ragged_dtype out_dt, void* stream) {
+int ragged_attn_strided(const void* q, const void* k, const void* v, void* o,
+                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
+                        int64_t in_tok_stride, int64_t out_tok_stride, float scale,
+                        ragged_dtype in_dt, ragged_dtype out_dt, void* stream) {
     if (!q || !k || !v || !o || !cu_seqlens) return RAGGED_ERR_NULL;
     if (B <= 0 || H <= 0 || D <= 0 || max_seqlen < 1) return RAGGED_ERR_SHAPE;
     // grid <= q-tiles * (B*H rounded up to a whole dispatch batch of 512) must fit a 32-bit grid
     const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)max_seqlen + 63) / 64);
     if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
+    const int64_t row = (int64_t)H * D;
+    if (in_tok_stride < row || out_tok_stride < row) return RAGGED_ERR_SHAPE;
     if (D != 64) return RAGGED_ERR_UNSUPPORTED;
     const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
                          (in_dt == RAGGED_BF16 && (out_dt == RAGGED_BF16 || out_dt == RAGGED_F32));
     if (!pair_ok || !isfinite(scale)) return RAGGED_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return RAGGED_ERR_UNSUPPORTED;
-    return from_hip(ragged::launch_attn(q, k, v, o, cu_seqlens, B, max_seqlen, H, scale, in_dt, out_dt,
+    // every token row must start on a 16-byte boundary
+    const int64_t out_bytes = out_dt == RAGGED_F32 ? 4 : 2;
+    if ((in_tok_stride * 2) % 16 != 0 || (out_tok_stride * out_bytes) % 16 != 0) return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_attn(q, k, v, o, cu_seqlens, B, max_seqlen, H, in_tok_stride,
+                                        out_tok_stride, scale, in_dt, out_dt,
                                         static_cast<hipStream_t>(stream)));
+}
+
+int ragged_attn(const void* q, const void* k, const void* v, void* o,
+                const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
+                float scale, ragged_dtype in_dt, ragged_dtype out_dt, void* stream) {
+    const int64_t row = (H > 0 && D > 0) ? (int64_t)H * D : 0;     // contiguous [T, H, D]
+    return ragged_attn_strided(q, k, v, o, cu_seqlens, B, max_seqlen, H, D, row, row, scale, in_dt, out_dt,
+                               stream);
 }
 
 int ragged_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
@@ -79,6 +94,25 @@ int ragged_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlen
                                           static_cast<hipStream_t>(stream)));
 }
 
+int ragged_repack(const void* packed_in, const uint8_t* keep_rows, const int32_t* cu_in, int B,
+                  int64_t cap_in, int C, ragged_dtype dt, void* packed_out, int64_t cap_out,
+                  int32_t* cu_out, int32_t* gather_out, void* stream) {
+    if (!packed_in || !keep_rows || !cu_in || !packed_out || !cu_out || !gather_out) return RAGGED_ERR_NULL;
+    if (B <= 0 || C <= 0 || cap_in > (int64_t)INT32_MAX - 64) return RAGGED_ERR_SHAPE;
+    if (!is16bit(dt) || (C & 7) != 0 || !aligned16(packed_in) || !aligned16(packed_out)) return RAGGED_ERR_UNSUPPORTED;
+    if (cap_in < 1 || cap_out < 1) return RAGGED_ERR_CAPACITY;
+    return from_hip(ragged::launch_repack(packed_in, keep_rows, cu_in, B, cap_in, C, packed_out, cap_out,
+                                          cu_out, gather_out, static_cast<hipStream_t>(stream)));
+}
+
+int ragged_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int C, ragged_dtype dt,
+                       void* out, void* stream) {
+    if (!packed || !cu_seqlens || !out) return RAGGED_ERR_NULL;
+    if (B <= 0 || C <= 0) return RAGGED_ERR_SHAPE;
+    if (!is16bit(dt) || (C & 7) != 0 || !aligned16(packed) || !aligned16(out)) return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_cls_extract(packed, cu_seqlens, B, C, out, static_cast<hipStream_t>(stream)));
+}
+
 int ragged_noop(int grid, void* stream) {
     if (grid < 1) return RAGGED_ERR_SHAPE;
     return from_hip(ragged::launch_noop(grid, static_cast<hipStream_t>(stream)));
@@ -90,7 +124,7 @@ const char* ragged_status_string(int status) {
         case RAGGED_ERR_NULL: return "a required pointer is NULL";
         case RAGGED_ERR_SHAPE: return "a dimension is non-positive or too large";
         case RAGGED_ERR_UNSUPPORTED: return "unsupported dtype, head dim, alignment, scale or fill mode";
-        case RAGGED_ERR_CAPACITY: return "cap_rows must be at least 1";
+        case RAGGED_ERR_CAPACITY: return "a row capacity must be at least 1";
         case RAGGED_ERR_HIP: return "the HIP runtime refused the launch";
         default: return "unknown";
     }

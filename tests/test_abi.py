@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() >= 200
+    assert binding.version() >= 300
     assert binding.status_string(0) == "ok"
     texts = {binding.status_string(s) for s in range(6)}
     assert len(texts) == 6 and binding.status_string(99) == "unknown"
@@ -91,6 +91,40 @@ def test_attn_padded_validation(lib):
     for bad in (dict(B=0), dict(N=0), dict(H=-1), dict(D=0), dict(B=1 << 20, N=1 << 20)):
         assert call(**bad) == 2
     for bad in (dict(D=32), dict(N=1537), dict(fm=2), dict(i=1, od=0), dict(scale=float("nan")), dict(v=FAKE + 8)):
+        assert call(**bad) == 3
+
+
+def test_attn_strided_validation(lib):
+    def call(q=FAKE, k=FAKE, v=FAKE, o=FAKE, cu=FAKE, B=2, ms=8, H=2, D=64, si=384, so=128, scale=0.125, i=0, od=0):
+        return lib.ragged_attn_strided(q, k, v, o, cu, B, ms, H, D, si, so, scale, i, od, None)
+    for null in ("q", "k", "v", "o", "cu"):
+        assert call(**{null: None}) == 1
+    for bad in (dict(B=0), dict(ms=0), dict(si=127), dict(so=64), dict(si=-384)):
+        assert call(**bad) == 2
+    for bad in (dict(D=32), dict(si=132), dict(so=132), dict(i=0, od=1), dict(scale=float("inf")), dict(k=FAKE + 2)):
+        assert call(**bad) == 3
+
+
+def test_repack_validation(lib):
+    def call(src=FAKE, kr=FAKE, cu=FAKE, B=2, cap_in=16, C=64, dt=0, dst=FAKE, cap_out=16, cuo=FAKE, gi=FAKE):
+        return lib.ragged_repack(src, kr, cu, B, cap_in, C, dt, dst, cap_out, cuo, gi, None)
+    for null in ("src", "kr", "cu", "dst", "cuo", "gi"):
+        assert call(**{null: None}) == 1
+    for bad in (dict(B=0), dict(C=0), dict(cap_in=1 << 31)):
+        assert call(**bad) == 2
+    for bad in (dict(dt=2), dict(C=12), dict(src=FAKE + 4), dict(dst=FAKE + 8)):
+        assert call(**bad) == 3
+    assert call(cap_in=0) == 4 and call(cap_out=0) == 4
+
+
+def test_cls_extract_validation(lib):
+    def call(src=FAKE, cu=FAKE, B=2, C=64, dt=0, out=FAKE):
+        return lib.ragged_cls_extract(src, cu, B, C, dt, out, None)
+    for null in ("src", "cu", "out"):
+        assert call(**{null: None}) == 1
+    for bad in (dict(B=0), dict(C=-8)):
+        assert call(**bad) == 2
+    for bad in (dict(dt=2), dict(C=20), dict(src=FAKE + 2), dict(out=FAKE + 8)):
         assert call(**bad) == 3
 
 
