@@ -194,3 +194,58 @@ class Pipeline:
     @property
     def tokens(self) -> int:
         return sum(w.T for w in self.layers)
+
+
+class StayPackedPipeline:
+    """The same 12 layers kept in the packed layout throughout (the paper's Section 4.3 flow): one
+    ragged_pack in front, per layer ragged_attn_strided on a fused [T_l, 3, H, D] QKV buffer, a
+    ragged_repack where the schedule prunes again, and ragged_cls_extract at the end.  As in
+    Pipeline there are no projection weights: each layer's QKV buffer is seeded data, and the
+    attention output is the row tensor that the next re-pack prunes."""
+
+    def __init__(self, layers):
+        import torch
+        from paper_2604_15408_amd import binding
+        from paper_2604_15408_amd import workloads as wl
+        self.torch, self.b, self.layers = torch, binding, layers
+        dev = "cuda:0"
+        w0 = layers[0]
+        B, N, C, H, D = w0.B, w0.N, w0.C, w0.H, w0.D
+        cap = B * N
+        self.x = w0.features().to(dev)
+        self.keep0 = w0.keep.to(dev)
+        row_masks = wl.pipeline_row_masks([w.keep for w in layers])
+        # a layer re-packs when its mask differs from the previous layer's
+        self.prunes = [l for l in range(1, len(layers)) if not bool(row_masks[l].all())]
+        self.row_keep = {l: torch.nn.functional.pad(row_masks[l], (0, cap - row_masks[l].numel())).to(dev)
+                         for l in self.prunes}
+        self.rows = [torch.zeros(cap, C, dtype=torch.float16, device=dev) for _ in range(2)]
+        self.cu = [torch.zeros(B + 1, dtype=torch.int32, device=dev) for _ in range(len(self.prunes) + 1)]
+        self.gidx = [torch.zeros(cap, dtype=torch.int32, device=dev) for _ in range(len(self.prunes) + 1)]
+        self.qkv = []
+        for w in layers:
+            q, k, v = w.qkv(max(w.T, 1))
+            self.qkv.append(torch.stack((q, k, v), dim=1).contiguous().to(dev))      # [T_l, 3, H, D]
+        self.o = [torch.zeros(max(w.T, 1), H, D, dtype=torch.float16, device=dev) for w in layers]
+        self.cls = torch.zeros(B, C, dtype=torch.float16, device=dev)
+        self.launches = 1 + len(layers) + len(self.prunes) + 1
+        torch.cuda.synchronize()
+
+    def run(self):
+        b, layers = self.b, self.layers
+        b.ragged_pack(self.x, self.keep0, self.rows[0], self.cu[0], self.gidx[0])
+        stage, cur = 0, 0
+        for l, w in enumerate(layers):
+            if l in self.prunes:
+                # the previous layer's output rows are pruned again, packed to packed
+                src = self.o[l - 1].view(-1, w.C)
+                b.ragged_repack(src, self.row_keep[l][: src.shape[0]], self.cu[stage], self.rows[1 - cur],
+                                self.cu[stage + 1], self.gidx[stage + 1])
+                stage, cur = stage + 1, 1 - cur
+            qkv = self.qkv[l]
+            b.ragged_attn_strided(qkv[:, 0], qkv[:, 1], qkv[:, 2], self.o[l], self.cu[stage], w.N, w.scale)
+        b.ragged_cls_extract(self.o[-1].view(-1, layers[-1].C), self.cu[stage], self.cls)
+
+    @property
+    def tokens(self) -> int:
+        return sum(w.T for w in self.layers)

@@ -5,7 +5,8 @@
 Cases: the headline batch; the bf16 pruning-ratio sweep next to a padded baseline of the same shape
 (this library's own attention kernel run with every image at the full N tokens -- the bytes and
 flops a padded dense attention has to spend, with no mask cost added); the 384x384 serving batches;
-the 12-layer progressive-pruning loop captured in ONE HIP graph.  Kernel times are HIP-event times
+the 12-layer progressive-pruning loop captured in ONE HIP graph, both through the padded tensor every
+layer (36 kernels) and staying packed (17 kernels).  Kernel times are HIP-event times
 of a graph holding 20 back-to-back copies of the kernel (divided by 20), so they include the
 in-graph kernel-to-kernel gap that an empty kernel shows separately.
 """
@@ -17,7 +18,8 @@ import os
 import sys
 
 from . import workloads as wl
-from .harness import REPLICAS, PaddedPath, Path, Pipeline, capture, event_time_us, wall_steps
+from .harness import (REPLICAS, PaddedPath, Path, Pipeline, StayPackedPipeline, capture, event_time_us,
+                      wall_steps)
 
 
 def stage_times(torch, p: Path):
@@ -74,6 +76,21 @@ def pipeline_case(torch):
             "tokens_per_s": pipe.tokens / (wall_graph * 1e-6)}
 
 
+def stay_packed_case(torch):
+    layers = wl.pipeline()
+    pipe = StayPackedPipeline(layers)
+    pipe.run()
+    torch.cuda.synchronize()
+    g = capture(torch, pipe.run)
+    us_graph = event_time_us(torch, g.replay, iters=30)[0]
+    wall_graph = wall_steps(torch, g.replay, 100) * 1e6
+    wall_eager = wall_steps(torch, pipe.run, 100) * 1e6
+    return {"case": "pipeline_12_layers_stay_packed", "B": layers[0].B, "N": layers[0].N,
+            "T_per_layer": [w.T for w in layers], "tokens": pipe.tokens, "kernels_in_graph": pipe.launches,
+            "graph_gpu_us": us_graph, "graph_wall_us": wall_graph, "eager_wall_us": wall_eager,
+            "tokens_per_s": pipe.tokens / (wall_graph * 1e-6)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default=None)
@@ -101,6 +118,7 @@ def main():
     for B in (1, 2, 4, 32):
         emit(case(torch, wl.serving_384(B), "serving_384"))
     emit(pipeline_case(torch))
+    emit(stay_packed_case(torch))
     if args.out:
         os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
         with open(args.out, "w") as f:

@@ -154,6 +154,16 @@ def pipeline_masks(B: int = 64, N: int = 197, layers: int = 12, ratio: float = 0
     return masks
 
 
+def pipeline_row_masks(masks: List[torch.Tensor]) -> List[torch.Tensor]:
+    """The same pruning schedule expressed on packed rows: entry l (l >= 1) holds one byte per row
+    that survived masks[l-1], set if the row also survives masks[l] (pure indexing of the masks;
+    entry 0 is masks[0] flattened, the first pack's own mask)."""
+    rows = [masks[0].reshape(-1).clone()]
+    for prev, cur in zip(masks[:-1], masks[1:]):
+        rows.append(cur.reshape(-1)[prev.reshape(-1) != 0].clone())
+    return rows
+
+
 def pipeline(seed: int = 1004) -> List[Workload]:
     """One Workload per layer of the 12-layer pipeline (B=64, N=197, C=768, fp16)."""
     masks = pipeline_masks(seed=seed)

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2604_15408_amd import workloads as wl
-from paper_2604_15408_amd.harness import Path, Pipeline, capture
+from paper_2604_15408_amd.harness import Path, Pipeline, StayPackedPipeline, capture
 from tests import helpers as hp
 
 pytestmark = pytest.mark.gpu
@@ -74,3 +74,60 @@ def test_twelve_layer_loop_in_one_graph_matches_eager_and_oracle():
     assert np.array_equal(wl.to_words(pipe.x[-1].cpu()), want_x)
     # tokens dropped at an earlier layer stay dropped: their rows are zero after the last unpack
     assert not pipe.x[-1][~w.keep.bool().to("cuda:0")].any()
+
+
+def test_stay_packed_loop_matches_the_unpack_pack_loop_and_oracle():
+    """Pack once, stay packed (strided attention, re-pack at the pruning layers, CLS read at the end):
+    same lengths and attention rows as the loop that goes through the padded tensor every layer."""
+    layers = _small_pipeline()
+    ref = Pipeline(layers, fill_mode=1)
+    ref.run()
+    sp = StayPackedPipeline(layers)
+    assert sp.prunes == [2, 5, 8] and sp.launches == 17
+    sp.run()
+    torch.cuda.synchronize()
+    eager = ([o.clone() for o in sp.o], [c.clone() for c in sp.cu], sp.cls.clone(), [r.clone() for r in sp.rows])
+
+    g = capture(torch, sp.run)
+    for rep in range(3):
+        for t in sp.o + sp.rows + [sp.cls]:
+            t.fill_(5.0)
+        for c in sp.cu:
+            c.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for l in range(12):
+            assert torch.equal(sp.o[l].view(torch.int16), eager[0][l].view(torch.int16))
+        for a, b in zip(sp.cu, eager[1]):
+            assert torch.equal(a, b)
+        assert torch.equal(sp.cls.view(torch.int16), eager[2].view(torch.int16))
+
+    # the same Q, K, V rows and lengths: attention outputs agree bit for bit with the padded-layout loop
+    for l, w in enumerate(layers):
+        assert torch.equal(sp.o[l][: w.T].view(torch.int16), ref.o[l][: w.T].view(torch.int16))
+    stage_layers = [0, 2, 5, 8]
+    for stage, l in enumerate(stage_layers):
+        assert sp.cu[stage].cpu().numpy().tolist() == hp.cu_from_lengths(layers[l].lengths).tolist()
+    # oracle: re-pack chain of layer outputs, composed gather index, CLS rows
+    for stage, l in enumerate(stage_layers[1:], start=1):
+        prev = layers[l - 1]
+        rows = wl.to_words(sp.o[l - 1][: prev.T].cpu()).reshape(prev.T, prev.C)
+        keep_rows = wl.pipeline_row_masks([w.keep for w in layers])[l].numpy()
+        want_rows, want_cu, want_gi = oracle.repack(rows, keep_rows, hp.cu_from_lengths(prev.lengths))
+        T = int(want_cu[-1])
+        assert T == layers[l].T
+        assert np.array_equal(sp.gidx[stage][:T].cpu().numpy(), want_gi)
+    last = layers[-1]
+    final_rows = wl.to_words(sp.o[-1][: last.T].cpu()).reshape(last.T, last.C)
+    want_cls = oracle.cls_extract(final_rows, hp.cu_from_lengths(last.lengths))
+    assert np.array_equal(wl.to_words(sp.cls.cpu()), want_cls)
+    # CLS is never pruned, so the CLS row equals token 0 of the padded-layout loop's final tensor
+    assert torch.equal(sp.cls.view(torch.int16), ref.x[-1][:, 0].contiguous().view(torch.int16))
+    # the last re-pack's rows (written at layer 9 from layer 8's output)
+    l = 8
+    prev = layers[l - 1]
+    rows = wl.to_words(sp.o[l - 1][: prev.T].cpu()).reshape(prev.T, prev.C)
+    want_rows, _, _ = oracle.repack(rows, wl.pipeline_row_masks([w.keep for w in layers])[l].numpy(),
+                                    hp.cu_from_lengths(prev.lengths))
+    assert np.array_equal(wl.to_words(sp.rows[1][: layers[l].T].cpu()), want_rows)
