@@ -96,7 +96,8 @@ int ragged_attn(const void* q, const void* k, const void* v, void* o,
  * q = base, k = base + H*D, v = base + 2*H*D with in_tok_stride = 3*H*D attends on it in place,
  * without three de-interleaving copies.  ragged_attn is this call with both strides = H*D.
  *
- * Strides are in elements of the respective dtype, must be >= H*D, and every token row must start
+ * Strides are in elements of the respective dtype, must be >= H*D (in_tok_stride also <= 2^23,
+ * else RAGGED_ERR_SHAPE), and every token row must start
  * on a 16-byte boundary (in_tok_stride a multiple of 8; out_tok_stride a multiple of 8 for 16-bit
  * outputs, of 4 for F32).  Everything else as for ragged_attn; outputs are bit-identical to
  * ragged_attn on contiguous copies of the same rows.

@@ -1,6 +1,7 @@
 // Bidirectional multi-head attention over a packed ragged buffer (Section 4.2, Algorithm 1), for
-// gfx950: one launch, one work-group per (image, head, 64-query tile), K/V tiles staged in LDS,
-// MFMA 16x16x32 for both contractions with fp32 accumulation, fp32 online softmax.
+// gfx950: one launch, one work-group per (image, head, 64-query tile), K/V tiles streamed through a
+// ring of LDS buffers by direct global->LDS loads, MFMA 16x16x32 for both contractions with fp32
+// accumulation, fp32 online softmax.
 //
 // Orientation.  Each wavefront owns 16 queries and computes the TRANSPOSED score tile
 // S^T = K Q^T (keys x queries).  In the MFMA result layout a lane then holds, for ONE query
@@ -14,17 +15,24 @@
 //   B: lane l holds col l%16,  k-slots 8*(l/16)+e
 //   D: lane l, register r holds row 4*(l/16)+r, col l%16
 // Which contraction index sits in which k-slot is free as long as A and B agree, and which logical
-// row/column an MFMA row/column stands for is free as long as loads and stores agree.  Both
-// freedoms are used to make every LDS access a conflict-free 16-byte one and every global access a
-// contiguous 32 bytes per lane:
-//   * Q (B operand of S^T): lane group g = l/16 loads head-dim elements 16g..16g+15 of its query.
-//   * K tile in LDS, row-major [key][d], row stride 72 halves; A operand = 8 halves at d = 16g+8s.
-//   * V tile in LDS TRANSPOSED, [rho][kappa], stride 72 halves, where
-//        rho(d)     = (d%4)*16 + d/4                      (row permutation of the head dim)
-//        kappa(key) = 32*(key/32) + 8*((key%16)/4) + 4*((key%32)/16) + key%4
-//     so that lane group g reads 8 consecutive kappa = exactly the keys whose probabilities it
-//     holds, and ends up owning output elements d = 16g .. 16g+15 of its query (32 contiguous
-//     bytes).  The transposition is done once per tile in registers while filling LDS.
+// row/column an MFMA row/column stands for is free as long as loads and stores agree.
+//
+// Data movement.  A K or V tile is 64 rows of 128 bytes, kept ROW-MAJOR in LDS exactly as the
+// hardware's global->LDS load writes it: one wavefront instruction moves 64 x 16 bytes and lane i's
+// bytes land at (wave-uniform base) + 16*i, with no register staging and no VALU work.  Which global
+// 16-byte chunk a lane fetches is free, and is used to swizzle: row r keeps chunk c at position
+// c ^ ((r>>1)&3).  With that
+//   * the A operand of S^T (lane: key l%16, head-dim chunk 2*(l/16)+ks) is one conflict-free
+//     16-byte LDS read;
+//   * the A operand of O^T needs V transposed (for one head-dim element, 8 keys): the transposing
+//     LDS read (ds_read_b64_tr_b16: inside a 16-lane group, lane l receives element l%4 of the four
+//     values read by lanes 4e + l/4, e = 0..3) delivers it from the row-major tile.  Lane sigma of
+//     group g reads key 4g + sigma/4 (+16 for the second half of a 32-key block), head-dim elements
+//     16*(sigma%4) + 4*dt .. +3, so lane l's MFMA row stands for element 16*(l%16/4) + 4*dt + l%4 and
+//     each lane ends up owning output elements 16g .. 16g+15 of its query (32 contiguous bytes).
+// Loads of tile t+kRing-1 are issued while tile t is computed (ring of kRing tiles); completion is
+// tracked with the vector-memory counter, one barrier per tile.  Measured: a ring of two (four
+// work-groups per CU) beats deeper rings, which cost resident wavefronts.
 //
 // bf16 inputs: Q K^T uses the bf16 MFMA (products are exact in fp32).  A bf16 probability would
 // carry only 8 significant bits, so P is split as P = P_hi + P_lo (two bf16 values, 16 bits
@@ -40,7 +48,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kHeadDim = 64;
 constexpr int kBN = 64;                 // keys per K/V tile
-constexpr int kLdsStride = 72;          // halves per LDS row: 64 + 8 of padding (144 bytes)
+// Work-group shape.  Measured on the dense layer (B=64, n=197) and the pruned batches: four
+// wavefronts with a ring of two tiles (32 KB, four work-groups per CU) is the fastest; deeper rings
+// (3, 4) lose resident wavefronts and gain nothing, eight-wavefront groups with rings of 2..4 tie
+// on dense batches and lose on short sequences.
+constexpr int kRing = 2;                // K/V tiles resident in LDS per work-group (2..4)
+constexpr int kAttnWaves = 4;           // wavefronts (16 queries each) per work-group: 4 or 8
+constexpr int kAttnThreads = kWaveSize * kAttnWaves;
+constexpr int kAttnOcc = kAttnWaves == 8 ? 2 : (kRing == 2 ? 4 : (kRing == 3 ? 3 : 2));  // work-groups per CU aimed at
+constexpr int kTileBytes = kBN * kHeadDim * 2;   // one K or one V tile: 8 KB
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazyLog2 = 8.0f;       // probabilities stay below 2^8 between rescales
 constexpr int kMaxGatherTokens = 1536;  // tokens per image the gather-on-load variant can index in LDS
@@ -134,15 +150,43 @@ __device__ __forceinline__ float quad_max(float x) {
     const unsigned b0 = b[0], b1 = b[1];
     return fmaxf(as_f32(b0), as_f32(b1));
 }
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) short4v lds_short4;
+
+__device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
+    const u32x4 w = *reinterpret_cast<const lds_u32x4*>(static_cast<uintptr_t>(addr));
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+// transposing 8-byte LDS read (see the header comment)
+__device__ __forceinline__ short4v lds_read_tr(uint32_t addr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4*>(static_cast<uintptr_t>(addr)));
+}
+
+// One wavefront instruction of the global->LDS load: lane i fetches the 16 bytes at base + voff and
+// the hardware stores them at LDS address lds_dst + 16*i.  The compiler is not told about the LDS
+// write; callers order it against LDS reads with wait_vm<>() and a barrier.
+__device__ __forceinline__ void dma16(uint32_t lds_dst, uint32_t voff, const void* base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_dst), "v"(voff), "s"(base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
 // One K/V tile (already in LDS) against this wavefront's 16 queries: S^T = K Q^T, online-softmax
 // update, O^T += V^T P^T.  NT = 16-key subtiles present in the tile (1..4); MASK: the last subtile may
-// hold keys past the end of the sequence (index >= rem), which are masked out.
+// hold keys past the end of the sequence (index >= rem), which are masked out (their LDS rows hold
+// a copy of the last real row, so they are finite wherever the inputs are).
+// k_a0/k_a1: this lane's LDS byte addresses of its K operand for the two 32-element k-steps of
+// subtile 0; v_a0/v_a1: of its transposed V read for head-dim blocks dt = 0,1 / 2,3 of key block 0.
 // scale_log2e >= 0 here (a negative softmax scale is folded into the sign of Q by the caller), so
 // the row maximum can be taken on the raw scores and the scale fused into the exponent's FMA.
 template <typename In, int NT, bool MASK>
-__device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
-                                            const uint16_t* __restrict__ vt_tile,
-                                            const typename In::vec8 (&q_frag)[2], int rem, int col, int g,
+__device__ __forceinline__ void tile_update(uint32_t k_a0, uint32_t k_a1, uint32_t v_a0, uint32_t v_a1,
+                                            const typename In::vec8 (&q_frag)[2], int rem, int g,
                                             float scale_log2e, float& m_run, f32x4& l_acc,
                                             f32x4 (&o_acc)[4]) {
     typedef typename In::vec8 vec8;
@@ -150,13 +194,10 @@ __device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
     f32x4 st[NT];
 #pragma unroll
     for (int kt = 0; kt < NT; ++kt) {
-        st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const uint4 a = *reinterpret_cast<const uint4*>(
-                &k_tile[(16 * kt + col) * kLdsStride + 16 * g + 8 * ks]);
-            st[kt] = In::mfma(as_vec8<vec8>(a), q_frag[ks], st[kt]);
-        }
+        const uint4 a0 = lds_read16(k_a0 + kt * 16 * 128);
+        const uint4 a1 = lds_read16(k_a1 + kt * 16 * 128);
+        st[kt] = In::mfma(as_vec8<vec8>(a0), q_frag[0], f32x4{0.f, 0.f, 0.f, 0.f});
+        st[kt] = In::mfma(as_vec8<vec8>(a1), q_frag[1], st[kt]);
     }
     // -------- online softmax (this lane: one query, keys 16*kt + 4*g + r of the tile)
     const int last_valid = rem - 16 * (NT - 1) - 4 * g;        // r < last_valid is a real key (last subtile)
@@ -192,9 +233,13 @@ __device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
     for (int bb = 0; bb < (NT + 1) / 2; ++bb) {
         uint4 vt[4];
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-            vt[dt] = *reinterpret_cast<const uint4*>(
-                &vt_tile[(16 * dt + col) * kLdsStride + 32 * bb + 8 * g]);
+        for (int dt = 0; dt < 4; ++dt) {
+            const uint32_t a = ((dt & 2) ? v_a1 : v_a0) + 8 * (dt & 1) + bb * 32 * 128;
+            const short4v lo = lds_read_tr(a);                  // keys 32bb      + 4g + 0..3
+            const short4v hi = lds_read_tr(a + 16 * 128);       // keys 32bb + 16 + 4g + 0..3
+            const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+            vt[dt] = make_uint4(lo2.x, lo2.y, hi2.x, hi2.y);
+        }
         float p[8];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -217,11 +262,10 @@ __device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
 //   * group * q_tiles is about what the chip holds resident, so in the dense case the q-tiles of a
 //     pair run together and their K/V re-reads hit L2 instead of going back to the fabric.
 //
-// A work-group has WAVES wavefronts of 16 queries each (q-tile = 16*WAVES rows).  K/V tiles of 64
-// keys are double-buffered in LDS and the next tile's global loads are issued before the current
-// tile is computed, so one barrier per tile suffices and the fabric latency of tile t+1 hides
-// behind the arithmetic of tile t.  The lower half of the threads copies K, the upper half
-// transposes V.
+// A work-group has four wavefronts of 16 queries each.  Wavefront w issues the loads of rows
+// 16w .. 16w+15 of every K and V tile (four instructions per tile); rows past the end of the
+// sequence fetch the last real row instead, and a wavefront whose rows lie beyond the 32-key blocks
+// the tile's arithmetic touches issues nothing.
 //
 // GATHER = false: q, k, v, o are packed [T, H, D] and image i owns rows [cu[i], cu[i+1]).
 // GATHER = true : q, k, v, o are padded [B, N, H, D]; the group first turns image i's keep mask
@@ -229,20 +273,19 @@ __device__ __forceinline__ void tile_update(const uint16_t* __restrict__ k_tile,
 //   and writes rows through that list, so pack and unpack need no launch of their own.  With
 //   fill_mode 1 the q-tile-0 group of every (image, head) also zeroes that head's slice of the
 //   dropped rows of o.
-template <typename In, typename OutT, int WAVES, bool GATHER>
-__global__ __launch_bounds__(kWaveSize * WAVES, 4)
+template <typename In, typename OutT, bool GATHER>
+__global__ __launch_bounds__(kAttnThreads, kAttnOcc < 1 ? 1 : kAttnOcc)
 void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                  const uint16_t* __restrict__ v, OutT* __restrict__ o,
                  const int32_t* __restrict__ cu_seqlens, const uint8_t* __restrict__ keep, int n_tok,
                  int fill_mode, int H, int64_t tok, int64_t tok_o, int pairs, int q_tiles, int group,
                  float scale_log2e, int negate_q) {
     typedef typename In::vec8 vec8;
+    constexpr int WAVES = kAttnWaves;
+    constexpr int kI = 8 / WAVES;                              // load instructions per wavefront per K (or V) tile
+    constexpr int kPer = 2 * kI;                               // ... per K+V tile
     constexpr int kBM = 16 * WAVES;                            // queries per work-group
-    constexpr int kHalf = 32 * WAVES;                          // threads per fill role
-    constexpr int kKLoads = 512 / kHalf;                       // 16-byte K units per K thread
-    constexpr int kKeyStep = kHalf / 8;                        // keys between a K thread's units
-    __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kBN * kLdsStride];
-    __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][kHeadDim * kLdsStride];
+    __shared__ __attribute__((aligned(1024))) uint4 ring[kRing * 2 * kTileBytes / 16];   // [slot][K|V]
 
     // bid = (batch * q_tiles + m_tile) * group + slot ; pair = batch * group + slot
     const int per_batch = q_tiles * group;
@@ -255,7 +298,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int img = pair / H;
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 15;                                 // query inside the wavefront's 16
     const int g = lane >> 4;                                   // lane group
     // tok / tok_o: elements between consecutive tokens of q, k, v / of o (H*64 when contiguous)
@@ -266,7 +309,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     __shared__ int wave_cnt[WAVES];
     int s, n;
     if (GATHER) {
-        constexpr int kThreads = kWaveSize * WAVES;
+        constexpr int kThreads = kAttnThreads;
         constexpr int kPre = 4;                                // mask bytes per thread requested up front
         const uint8_t* mask = keep + (int64_t)img * n_tok;
         s = img * n_tok;
@@ -309,80 +352,48 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         s = cu_seqlens[img];
         n = cu_seqlens[img + 1] - s;
     }
+    n = __builtin_amdgcn_readfirstlane(n);
     if (m0 >= n) return;                                       // whole group exits together
     // row of the j-th token of this image in q / k / v / o
     auto row_of = [&](int j) -> int64_t { return GATHER ? (int64_t)s + idx_lds[j] : (int64_t)s + j; };
     const bool wave_active = m0 + wave * 16 < n;               // wavefront has at least one real query
 
-    // ---- tile-fill roles
-    const bool fills_k = tid < kHalf;
-    const int fill = fills_k ? tid : tid - kHalf;
-    // K thread: 16-byte units (key = fill/8 + kKeyStep*a, dims 8*(fill%8) ..)
-    // V thread, WAVES == 4: keys 4*(fill/8)  .. +3, dims 8*(fill%8)  .. +7  (4 x 16-byte loads)
-    //           WAVES == 8: keys 4*(fill/16) .. +3, dims 4*(fill%16) .. +3  (4 x  8-byte loads)
-    // The key group of a V thread takes its bit 2 (which 16-key half of a 32-key block, i.e. which
-    // 8-byte half of a 16-byte LDS unit) from lane bit 3, so that the 32 lanes of a half-wavefront
-    // spread their 8-byte transposed writes evenly over all LDS banks.
-    const int v_slot = (WAVES == 4) ? fill >> 3 : fill >> 4;   // 0..15
-    const int v_kg = (v_slot & 8) | ((v_slot & 1) << 2) | ((v_slot >> 1) & 3);
-    const int v_d0 = (WAVES == 4) ? 8 * (fill & 7) : 4 * (fill & 15);
-    const uint16_t* fill_src = fills_k ? k + head_off + 8 * (fill & 7) : v + head_off + v_d0;
-    const int fill_key0 = fills_k ? (fill >> 3) : 4 * v_kg;
-    const int fill_dkey = fills_k ? kKeyStep : 1;
-    // V thread's 4 keys occupy 4 consecutive kappa slots
-    const int kappa = 32 * ((4 * v_kg) >> 5) + 8 * (((4 * v_kg) & 15) >> 2) + 4 * (((4 * v_kg) & 31) >> 4);
-
-    constexpr int kLoads = 4;                                  // both roles issue <= 4 loads per tile
-    uint4 raw[kLoads];
-    auto prefetch = [&](int j0) {
-        const int rem = n - j0;
+    // ---- K/V tile loads.  Instruction i (0, 1) of this wavefront covers tile rows 16*wave + 8i + lane/8;
+    // the lane's LDS slot is position lane%8 of that row, which holds chunk (lane%8) ^ ((row>>1)&3).
+    const uint32_t ring0 = (uint32_t)reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) void*)ring);
+    const uint32_t tok_bytes = (uint32_t)tok * 2u;
+    const int load_key = 8 * kI * wave + (lane >> 3);          // + 8i
+    const uint32_t load_chunk = 16u * ((lane & 7) ^ ((lane >> 4) & 3));
+    const uint16_t* k_base = k + (int64_t)s * tok + head_off;   // wave-uniform
+    const uint16_t* v_base = v + (int64_t)s * tok + head_off;
+    // Returns the number of load instructions issued (0 or kPer).  The per-lane offset is 32 bits wide:
+    // packed rows are addressed relative to the tile's first row (the 64-bit part is wave-uniform),
+    // gathered rows relative to the image's first token (the host checks that N tokens fit).
+    auto issue = [&](int t, int slot) -> int {
+        const int rem = n - t * kBN;
+        const int need_rows = rem >= kBN ? kBN : 32 * ((rem + 31) >> 5);   // rows the tile's MFMAs touch
+        if (8 * kI * wave >= need_rows) return 0;
+        const uint32_t dst = ring0 + slot * 2 * kTileBytes + wave * (1024 * kI);
+        const int64_t tile_off = GATHER ? 0 : (int64_t)t * kBN * tok;
 #pragma unroll
-        for (int a = 0; a < kLoads; ++a) {
-            raw[a] = make_uint4(0, 0, 0, 0);                   // keys past n are zero in LDS
-            if (fills_k && a >= kKLoads) continue;
-            const int key = fill_key0 + fill_dkey * a;         // key of the tile this load fetches
-            if (rem >= kBN || key < rem) {
-                const uint16_t* src = fill_src + row_of(j0 + key) * tok;
-                if (WAVES == 4 || fills_k) {
-                    raw[a] = *reinterpret_cast<const uint4*>(src);
-                } else {
-                    const uint2 two = *reinterpret_cast<const uint2*>(src);
-                    raw[a].x = two.x;
-                    raw[a].y = two.y;
-                }
-            }
+        for (int i = 0; i < kI; ++i) {
+            int rel = load_key + 8 * i;
+            rel = rel < rem ? rel : rem - 1;                    // past the end: the last real row again
+            const uint32_t row = GATHER ? (uint32_t)idx_lds[t * kBN + rel] : (uint32_t)rel;
+            const uint32_t voff = row * tok_bytes + load_chunk;
+            dma16(dst + i * 1024, voff, k_base + tile_off);
+            dma16(dst + i * 1024 + kTileBytes, voff, v_base + tile_off);
         }
-    };
-    auto stage = [&](int buf) {
-        if (fills_k) {
-#pragma unroll
-            for (int a = 0; a < kKLoads; ++a)
-                *reinterpret_cast<uint4*>(
-                    &k_lds[buf][((fill >> 3) + kKeyStep * a) * kLdsStride + 8 * (fill & 7)]) = raw[a];
-        } else {
-            constexpr int kDims = (WAVES == 4) ? 8 : 4;        // head-dim elements this thread transposes
-            const uint32_t w[4][4] = {{raw[0].x, raw[0].y, raw[0].z, raw[0].w},
-                                      {raw[1].x, raw[1].y, raw[1].z, raw[1].w},
-                                      {raw[2].x, raw[2].y, raw[2].z, raw[2].w},
-                                      {raw[3].x, raw[3].y, raw[3].z, raw[3].w}};
-#pragma unroll
-            for (int e = 0; e < kDims; ++e) {
-                const int d = v_d0 + e;
-                const int rho = (d & 3) * 16 + (d >> 2);
-                uint2 packed4;
-                if (e & 1) {
-                    packed4.x = (w[0][e >> 1] >> 16) | (w[1][e >> 1] & 0xffff0000u);
-                    packed4.y = (w[2][e >> 1] >> 16) | (w[3][e >> 1] & 0xffff0000u);
-                } else {
-                    packed4.x = (w[0][e >> 1] & 0xffffu) | (w[1][e >> 1] << 16);
-                    packed4.y = (w[2][e >> 1] & 0xffffu) | (w[3][e >> 1] << 16);
-                }
-                *reinterpret_cast<uint2*>(&vt_lds[buf][rho * kLdsStride + kappa]) = packed4;
-            }
-        }
+        return kPer;
     };
 
-    prefetch(0);
+    const int tiles = (n + kBN - 1) / kBN;
+    // c_next[d] = load instructions this wavefront has in flight for tile t+1+d (prologue: tiles 1 .. kRing-2)
+    int c_next[kRing > 2 ? kRing - 2 : 1] = {0};
+    issue(0, 0);
+#pragma unroll
+    for (int d = 0; d < kRing - 2; ++d) c_next[d] = d + 1 < tiles ? issue(d + 1, d + 1) : 0;
 
     // ---- Q: this lane's query row, head-dim elements 16g .. 16g+15 (zeros past the sequence end)
     const int q_row = m0 + wave * 16 + col;
@@ -401,46 +412,64 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
     const vec8 q_frag[2] = {as_vec8<vec8>(q_raw[0]), as_vec8<vec8>(q_raw[1])};
 
+    // ---- LDS read addresses of this lane inside a tile (see the header comment)
+    //   K operand: row col (+16kt), chunk 2g + ks at position (2g + ks) ^ ((col>>1)&3)
+    const uint32_t k_rel0 = col * 128 + 16 * ((2 * g) ^ ((col >> 1) & 3));
+    //   V transposed read: row 4g + sigma/4 (+32bb, +16), chunk 2*(sigma%4) + (dt>>1), half dt&1
+    const int sigma = col;
+    const int v_row = 4 * g + (sigma >> 2);
+    const uint32_t v_rel0 = v_row * 128 + 16 * ((2 * (sigma & 3)) ^ ((v_row >> 1) & 3)) + kTileBytes;
+
     float m_run = -INFINITY;                                   // running max (log2 domain)
     f32x4 l_acc = f32x4{0.f, 0.f, 0.f, 0.f};                   // running row sum (every register equal)
     f32x4 o_acc[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) o_acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int tiles = (n + kBN - 1) / kBN;
+    int slot = 0;                                              // ring slot of tile t
     for (int t = 0; t < tiles; ++t) {
-        const int buf = t & 1;
-        stage(buf);                         // buffer `buf` was last read two tiles ago: see barrier below
+        // this wavefront's part of tile t has landed once only the later tiles' loads remain in flight
+        int behind = 0;
+#pragma unroll
+        for (int d = 0; d < kRing - 2; ++d) behind += c_next[d];
+        if (behind == 0) wait_vm<0>();
+        else if (behind == kPer) wait_vm<kPer>();
+        else if (behind == 2 * kPer) wait_vm<2 * kPer>();
+        else wait_vm<3 * kPer>();
         __syncthreads();                    // tile t visible; every wavefront is past tile t-1's reads
-        if (t + 1 < tiles) prefetch((t + 1) * kBN);
+        const int slot_new = slot == 0 ? kRing - 1 : slot - 1; // slot of tile t-1, just freed, takes tile t+kRing-1
+        const int c_new = t + kRing - 1 < tiles ? issue(t + kRing - 1, slot_new) : 0;
+#pragma unroll
+        for (int d = 0; d + 1 < kRing - 2; ++d) c_next[d] = c_next[d + 1];
+        if (kRing > 2) c_next[kRing - 3] = c_new;
         if (wave_active) {
             const int rem = n - t * kBN;
-            const uint16_t* kt_ = k_lds[buf];
-            const uint16_t* vt_ = vt_lds[buf];
+            const uint32_t tile0 = ring0 + slot * 2 * kTileBytes;
+            const uint32_t k_a0 = tile0 + k_rel0, k_a1 = tile0 + (k_rel0 ^ 16u);
+            const uint32_t v_a0 = tile0 + v_rel0, v_a1 = tile0 + (v_rel0 ^ 16u);
             if (rem >= kBN) {
-                tile_update<In, 4, false>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc);
+                tile_update<In, 4, false>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc);
             } else {
                 switch ((rem + 15) >> 4) {
-                    case 1: tile_update<In, 1, true>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc); break;
-                    case 2: tile_update<In, 2, true>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc); break;
-                    case 3: tile_update<In, 3, true>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc); break;
-                    default: tile_update<In, 4, true>(kt_, vt_, q_frag, rem, col, g, scale_log2e, m_run, l_acc, o_acc); break;
+                    case 1: tile_update<In, 1, true>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                    case 2: tile_update<In, 2, true>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                    case 3: tile_update<In, 3, true>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                    default: tile_update<In, 4, true>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
                 }
             }
         }
+        slot = slot == kRing - 1 ? 0 : slot + 1;
     }
 
-    // ---- normalise and store: this lane owns d = 16g + 4r + dt of its query
-    if (wave_active) {
-        if (q_row < n) {
-            const float inv = 1.0f / l_acc[0];
-            float out16[16];
+    // ---- normalise and store: this lane owns d = 16g + 4dt + r of its query
+    if (wave_active && q_row < n) {
+        const float inv = 1.0f / l_acc[0];
+        float out16[16];
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) out16[4 * r + dt] = o_acc[dt][r] * inv;
-            store16(o + row_of(q_row) * tok_o + head_off + 16 * g, out16);
-        }
+            for (int r = 0; r < 4; ++r) out16[4 * dt + r] = o_acc[dt][r] * inv;
+        store16(o + row_of(q_row) * tok_o + head_off + 16 * g, out16);
     }
 }
 
@@ -449,15 +478,15 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
                         const int32_t* cu_seqlens, const uint8_t* keep, int n_tok, int fill_mode,
                         int B, int max_seqlen, int H, int64_t in_tok, int64_t out_tok, float scale,
                         hipStream_t stream) {
-    constexpr int kWaves = 4;                                  // 64 query rows per work-group
+    constexpr int kWaves = kAttnWaves;                         // 16 query rows each
     constexpr int kGroup = 512;                                // pairs per dispatch batch
     const int q_tiles = (max_seqlen + 16 * kWaves - 1) / (16 * kWaves);
     const int pairs = B * H;
     const int pairs8 = (pairs + kXcds - 1) / kXcds * kXcds;
     const int group = pairs8 < kGroup ? pairs8 : kGroup;
     const int batches = (pairs + group - 1) / group;
-    hipLaunchKernelGGL((attn_kernel<In, OutT, kWaves, GATHER>), dim3(batches * q_tiles * group),
-                       dim3(kWaveSize * kWaves), 0, stream,
+    hipLaunchKernelGGL((attn_kernel<In, OutT, GATHER>), dim3(batches * q_tiles * group),
+                       dim3(kAttnThreads), 0, stream,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                        static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, keep, n_tok,
                        fill_mode, H, in_tok, out_tok, pairs, q_tiles, group, fabsf(scale) * kLog2e,

@@ -42,7 +42,8 @@ int ragged_attn_strided(const void* q, const void* k, const void* v, void* o,
     const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)max_seqlen + 63) / 64);
     if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
     const int64_t row = (int64_t)H * D;
-    if (in_tok_stride < row || out_tok_stride < row) return RAGGED_ERR_SHAPE;
+    // the kernel addresses the 64 rows of a K/V tile with 32-bit byte offsets
+    if (in_tok_stride < row || out_tok_stride < row || in_tok_stride > (int64_t)1 << 23) return RAGGED_ERR_SHAPE;
     if (D != 64) return RAGGED_ERR_UNSUPPORTED;
     const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
                          (in_dt == RAGGED_BF16 && (out_dt == RAGGED_BF16 || out_dt == RAGGED_F32));
@@ -72,6 +73,8 @@ int ragged_attn_padded(const void* q, const void* k, const void* v, void* o, con
     const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)N + 63) / 64);
     if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
     if (D != 64 || N > ragged::attn_padded_max_tokens()) return RAGGED_ERR_UNSUPPORTED;
+    // the kernel addresses the N rows of an image with 32-bit byte offsets
+    if ((int64_t)N * H * D * 2 >= (int64_t)1 << 31) return RAGGED_ERR_SHAPE;
     if (fill_mode != 0 && fill_mode != 1) return RAGGED_ERR_UNSUPPORTED;
     const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
                          (in_dt == RAGGED_BF16 && (out_dt == RAGGED_BF16 || out_dt == RAGGED_F32));

@@ -99,7 +99,7 @@ def test_attn_strided_validation(lib):
         return lib.ragged_attn_strided(q, k, v, o, cu, B, ms, H, D, si, so, scale, i, od, None)
     for null in ("q", "k", "v", "o", "cu"):
         assert call(**{null: None}) == 1
-    for bad in (dict(B=0), dict(ms=0), dict(si=127), dict(so=64), dict(si=-384)):
+    for bad in (dict(B=0), dict(ms=0), dict(si=127), dict(so=64), dict(si=-384), dict(si=(1 << 23) + 8)):
         assert call(**bad) == 2
     for bad in (dict(D=32), dict(si=132), dict(so=132), dict(i=0, od=1), dict(scale=float("inf")), dict(k=FAKE + 2)):
         assert call(**bad) == 3
