@@ -4,7 +4,9 @@
 
 A "step" is one pass of the whole path over one synthetic batch: ragged_pack (keep mask ->
 cu_seqlens, gather indices, packed rows), ragged_attn on seeded Q/K/V of the packed length using
-the cu_seqlens pack just wrote, ragged_unpack of the attention output with pack's gather indices.
+the cu_seqlens pack just wrote, ragged_unpack of the attention output with pack's gather indices --
+issued either as those three launches or as ragged_pack_attn_unpack, one launch that produces the
+same outputs bit for bit; the fastest way is reported and named in config.launch.
 Inputs are resident in HBM before the timed region.  The default workload is the headline one:
 DeiT-Base attention geometry (N=197, H=12, D=64), B=32, 80 % pruned (keep probability 0.2), fp16.
 
@@ -67,25 +69,31 @@ def run(args):
     p = Path(w, args.fill_mode)
     alg = p.algorithmic()
 
-    # ---- whole path, three ways of issuing the same three kernels per step:
-    #   hipgraph        one hipGraphLaunch of the captured pipeline
-    #   eager           three checked binding calls (tensor checks + marshalling every call)
-    #   eager_prepared  three calls with pre-marshalled arguments
+    # ---- whole path (every output of pack, attn and unpack), issued in five ways:
+    #   hipgraph            one hipGraphLaunch of the captured three-kernel pipeline
+    #   eager               three checked binding calls (tensor checks + marshalling every call)
+    #   eager_prepared      three calls with pre-marshalled arguments
+    #   one_launch          ragged_pack_attn_unpack: the three stages in one kernel, checked call
+    #   one_launch_prepared the same with pre-marshalled arguments
     g_step = capture(torch, p.step)
     lean_step = p.prepared_step()
+    lean_one = p.prepared_one_launch()
     for _ in range(args.warmup):
         g_step.replay()
         p.step()
         lean_step()
+        lean_one()
     t_modes = {"hipgraph": wall_steps(torch, g_step.replay, args.steps),
                "eager": wall_steps(torch, p.step, args.steps),
-               "eager_prepared": wall_steps(torch, lean_step, args.steps)}
+               "eager_prepared": wall_steps(torch, lean_step, args.steps),
+               "one_launch": wall_steps(torch, p.one_launch, args.steps),
+               "one_launch_prepared": wall_steps(torch, lean_one, args.steps)}
     mode = min(t_modes, key=t_modes.get)
     t_step = t_modes[mode]
 
     # ---- each kernel alone: REPLICAS back-to-back copies in one graph, HIP events around a replay
     stage_us, stage_mean_us = {}, {}
-    for name, fn in (("pack", p.pack), ("attn", p.attn), ("unpack", p.unpack)):
+    for name, fn in (("pack", p.pack), ("attn", p.attn), ("unpack", p.unpack), ("pack_attn_unpack", p.one_launch)):
         g = capture(torch, fn, REPLICAS)
         med, mean = event_time_us(torch, g.replay, iters=max(20, args.steps // 10))
         stage_us[name], stage_mean_us[name] = med / REPLICAS, mean / REPLICAS
@@ -120,7 +128,12 @@ def run(args):
             traffic = json.load(f).get(w.name, {})
     except OSError:
         pass
-    dominant = max(stage_us, key=stage_us.get)
+    # the kernel the reported step spends its time in: the single-launch kernel if that is how the step
+    # was issued, else the slowest of the three
+    if mode.startswith("one_launch"):
+        dominant = "pack_attn_unpack"
+    else:
+        dominant = max(("pack", "attn", "unpack"), key=stage_us.get)
     dom_us = stage_mean_us[dominant]
     achieved = alg[dominant]["bytes"] / (dom_us * 1e-6) / 1e9
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
@@ -146,6 +159,7 @@ def run(args):
             "step_wall_us": {k: v * 1e6 for k, v in t_modes.items()},
             "attn_mfma_tflops": attn_tflops, "attn_mfma_frac": attn_tflops / MFMA_F16_PEAK_TFLOPS,
             "stage_gbs": {k: alg[k]["bytes"] / (stage_us[k] * 1e-6) / 1e9 for k in stage_us},
+            "three_launch_tokens_per_s": w.T / min(t_modes["hipgraph"], t_modes["eager"], t_modes["eager_prepared"]),
             "fused_single_launch": {"entry": "ragged_attn_padded", "kernel_us": fused_kernel_us,
                                     "wall_us_per_layer": fused_wall_us,
                                     "tokens_per_s": w.T / (fused_wall_us * 1e-6)},

@@ -36,7 +36,7 @@ typedef enum {
     RAGGED_ERR_SHAPE = 2,        /* a dimension is <= 0, overflows int32 row indexing, or a token
                                     stride is shorter than a row                                  */
     RAGGED_ERR_UNSUPPORTED = 3,  /* dtype pair, head dim, alignment or fill mode not supported    */
-    RAGGED_ERR_CAPACITY = 4,     /* a row capacity (cap_rows, cap_in, cap_out) is < 1             */
+    RAGGED_ERR_CAPACITY = 4,     /* a row capacity is < 1 (ragged_pack_attn_unpack: < B*N)        */
     RAGGED_ERR_HIP = 5           /* the HIP runtime refused the launch                            */
 } ragged_status;
 
@@ -143,6 +143,31 @@ int ragged_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlen
 int ragged_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
                        int B, int N, int H, int D, float scale, ragged_dtype in_dt,
                        ragged_dtype out_dt, int fill_mode, void* stream);
+
+/*
+ * ragged_pack_attn_unpack -- ragged_pack, ragged_attn and ragged_unpack of one layer (the three
+ * stages of Section 4) in ONE launch, with every output of the three calls produced and bit-identical
+ * to theirs.  Section 3 and Section 4.2 ("Why dispatch overhead is lower") argue that at ViT sizes the
+ * number of dispatches sets the latency; this entry point is that argument applied to the paper's
+ * own pipeline.  Each work-group (image, head, 64-query tile) recounts the image's first packed row
+ * and its kept-token list from the keep mask, so there is no dependency between work-groups.
+ *
+ *   x          [B, N, C]      padded features (dt), C = H*D
+ *   keep       [B, N]         one byte per token, nonzero = keep
+ *   q, k, v    [cap_rows, H, D]  ALREADY packed query / key / value rows (dt); rows [0, T) are read
+ *   packed     [cap_rows, C]  out: as from ragged_pack(x, keep)
+ *   cu_seqlens [B + 1]        out: as from ragged_pack
+ *   gather_idx [cap_rows]     out: as from ragged_pack
+ *   o          [cap_rows, H, D]  out (dt): as from ragged_attn(q, k, v, cu_seqlens)
+ *   out        [B, N, C]      out: as from ragged_unpack(o, ..., fill_mode)
+ *
+ * Supported: D = 64, N <= 1536, dt = F16 or BF16 (o has the input dtype).  cap_rows must be >= B*N
+ * (RAGGED_ERR_CAPACITY otherwise), so nothing can overflow.  x, packed, o, out must not overlap.
+ */
+int ragged_pack_attn_unpack(const void* x, const uint8_t* keep, const void* q, const void* k, const void* v,
+                            int B, int N, int H, int D, float scale, ragged_dtype dt, void* packed,
+                            int64_t cap_rows, int32_t* cu_seqlens, int32_t* gather_idx, void* o, void* out,
+                            int fill_mode, void* stream);
 
 /*
  * ragged_repack -- a second pruning decision applied to rows that are ALREADY packed.  Section 4.3

@@ -20,7 +20,7 @@ RAGGED_F16, RAGGED_BF16, RAGGED_F32 = 0, 1, 2
 _DTYPE_CODE = {torch.float16: RAGGED_F16, torch.bfloat16: RAGGED_BF16, torch.float32: RAGGED_F32}
 
 EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_strided", "ragged_attn_padded", "ragged_unpack",
-           "ragged_repack", "ragged_cls_extract", "ragged_noop", "ragged_status_string", "ragged_version")
+           "ragged_repack", "ragged_cls_extract", "ragged_pack_attn_unpack", "ragged_noop", "ragged_status_string", "ragged_version")
 
 _lib = None
 
@@ -51,6 +51,9 @@ def load() -> ctypes.CDLL:
         lib.ragged_repack.restype = i32
         lib.ragged_cls_extract.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         lib.ragged_cls_extract.restype = i32
+        lib.ragged_pack_attn_unpack.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, i64, vp, vp,
+                                                vp, vp, i32, vp]
+        lib.ragged_pack_attn_unpack.restype = i32
         lib.ragged_attn_padded.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, i32, vp]
         lib.ragged_attn_padded.restype = i32
         lib.ragged_unpack.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
@@ -201,6 +204,32 @@ def ragged_attn_padded(q, k, v, o, keep, scale: float, fill_mode: int = 0, strea
     """q,k,v,o [B,N,H,D], keep [B,N]: pack + attention + unpack of one layer in a single launch."""
     _check("ragged_attn_padded",
            load().ragged_attn_padded(*_attn_padded_args(q, k, v, o, keep, scale, fill_mode, stream)))
+
+
+def _step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream):
+    B, N, C = x.shape
+    cap, H, D = q.shape
+    return (_dev(x, "x", (torch.float16, torch.bfloat16)), _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)),
+            _dev(q, "q", x.dtype), _dev(k, "k", x.dtype, q.shape), _dev(v, "v", x.dtype, q.shape),
+            B, N, H, D, float(scale), _DTYPE_CODE[x.dtype], _dev(packed, "packed", x.dtype, (cap, C)), cap,
+            _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
+            _dev(gather_idx, "gather_idx", torch.int32, (cap,)), _dev(o, "o", x.dtype, q.shape),
+            _dev(out, "out", x.dtype, (B, N, C)), int(fill_mode), _stream(stream))
+
+
+def ragged_pack_attn_unpack(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale: float,
+                            fill_mode: int = 0, stream=None) -> None:
+    """ragged_pack(x, keep) + ragged_attn(q, k, v) + ragged_unpack(o -> out) in one launch; q, k, v,
+    o, packed, gather_idx hold cap >= B*N rows."""
+    _check("ragged_pack_attn_unpack", load().ragged_pack_attn_unpack(
+        *_step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream)))
+
+
+def prepare_pack_attn_unpack(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale: float,
+                             fill_mode: int = 0, stream=None) -> "Prepared":
+    return Prepared("ragged_pack_attn_unpack", load().ragged_pack_attn_unpack,
+                    _step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream),
+                    (x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out))
 
 
 def ragged_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> None:

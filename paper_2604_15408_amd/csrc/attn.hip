@@ -38,6 +38,7 @@
 // carry only 8 significant bits, so P is split as P = P_hi + P_lo (two bf16 values, 16 bits
 // together) and P V is two MFMAs; V stays exact.  The path is not MFMA-bound at ViT lengths.
 #include "common.h"
+#include "mask_prefix.h"
 
 namespace ragged {
 namespace {
@@ -267,20 +268,43 @@ __device__ __forceinline__ void tile_update(uint32_t k_a0, uint32_t k_a1, uint32
 // sequence fetch the last real row instead, and a wavefront whose rows lie beyond the 32-key blocks
 // the tile's arithmetic touches issues nothing.
 //
-// GATHER = false: q, k, v, o are packed [T, H, D] and image i owns rows [cu[i], cu[i+1]).
-// GATHER = true : q, k, v, o are padded [B, N, H, D]; the group first turns image i's keep mask
+// MODE kPacked: q, k, v, o are packed [T, H, D] and image i owns rows [cu[i], cu[i+1]).
+// MODE kPadded: q, k, v, o are padded [B, N, H, D]; the group first turns image i's keep mask
 //   into the list of kept token positions (ballot + prefix over the group, in LDS) and then reads
 //   and writes rows through that list, so pack and unpack need no launch of their own.  With
 //   fill_mode 1 the q-tile-0 group of every (image, head) also zeroes that head's slice of the
 //   dropped rows of o.
-template <typename In, typename OutT, bool GATHER>
+// MODE kStep  : the whole pack -> attention -> unpack step in this one launch.  q, k, v, o are
+//   packed as in kPacked, but the image's first row s is recounted from the keep mask (nonzero
+//   bytes before the image) and the kept-position list is built as in kPadded.  Besides its
+//   attention rows the group (image, head, q-tile) moves that head's 128-byte slice of its 64 rows
+//   from x to the packed buffer and writes each output row twice: to o (packed) and to its padded
+//   position in `out`.  Head-0 groups also write gather_idx, and q-tile 0 of head 0 writes
+//   cu_seqlens.  Every group derives s and the list itself, so no group waits for another.
+enum { kPacked = 0, kPadded = 1, kStep = 2 };
+
+// Extra operands of MODE kStep (null / zero otherwise).
+struct StepArgs {
+    const uint16_t* x;          // [B, N, C] padded features
+    uint16_t* packed;           // [cap_rows, C]
+    uint16_t* out;              // [B, N, C]
+    int32_t* cu_seqlens;        // [B + 1]
+    int32_t* gather_idx;        // [cap_rows]
+    int64_t cap_rows;
+};
+
+template <typename In, typename OutT, int MODE>
 __global__ __launch_bounds__(kAttnThreads, kAttnOcc < 1 ? 1 : kAttnOcc)
 void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                  const uint16_t* __restrict__ v, OutT* __restrict__ o,
                  const int32_t* __restrict__ cu_seqlens, const uint8_t* __restrict__ keep, int n_tok,
                  int fill_mode, int H, int64_t tok, int64_t tok_o, int pairs, int q_tiles, int group,
-                 float scale_log2e, int negate_q) {
+                 float scale_log2e, int negate_q, StepArgs step) {
     typedef typename In::vec8 vec8;
+    constexpr bool GATHER = MODE == kPadded;                   // q, k, v, o rows addressed through the kept list
+    constexpr bool LIST = MODE != kPacked;                     // the kept list is built from the mask
+    static_assert(MODE != kStep || (kAttnThreads == kBlockThreads && kAttnWaves == 4),
+                  "the mask prefix count and the x copy of kStep assume 256 threads and 64-row q-tiles");
     constexpr int WAVES = kAttnWaves;
     constexpr int kI = 8 / WAVES;                              // load instructions per wavefront per K (or V) tile
     constexpr int kPer = 2 * kI;                               // ... per K+V tile
@@ -305,19 +329,29 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int64_t head_off = (int64_t)h * kHeadDim;
     const int m0 = m_tile * kBM;
 
-    __shared__ uint16_t idx_lds[GATHER ? kMaxGatherTokens : 1];    // kept token positions, ascending
+    __shared__ uint16_t idx_lds[LIST ? kMaxGatherTokens : 1];      // kept token positions, ascending
     __shared__ int wave_cnt[WAVES];
+    __shared__ int lds4[4];
     int s, n;
-    if (GATHER) {
+    if (LIST) {
         constexpr int kThreads = kAttnThreads;
         constexpr int kPre = 4;                                // mask bytes per thread requested up front
         const uint8_t* mask = keep + (int64_t)img * n_tok;
         s = img * n_tok;
+        PrefixLoads before_image;
+        if (MODE == kStep) before_image = prefix_issue(keep, img * n_tok);   // requested with the image's own mask
         if (fill_mode == 1 && m_tile == 0) {                   // zero this head's slice of dropped rows
-            constexpr int kChunks = kHeadDim * (int)sizeof(OutT) / 16;
-            for (int t = tid / kChunks; t < n_tok; t += kThreads / kChunks)
-                if (mask[t] == 0)
-                    reinterpret_cast<uint4*>(o + (s + t) * tok_o + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
+            if (MODE == kStep) {
+                for (int t = tid / 8; t < n_tok; t += kThreads / 8)
+                    if (mask[t] == 0)
+                        reinterpret_cast<uint4*>(step.out + (int64_t)(s + t) * tok_o + head_off)[tid % 8] =
+                            make_uint4(0, 0, 0, 0);
+            } else {
+                constexpr int kChunks = kHeadDim * (int)sizeof(OutT) / 16;
+                for (int t = tid / kChunks; t < n_tok; t += kThreads / kChunks)
+                    if (mask[t] == 0)
+                        reinterpret_cast<uint4*>(o + (s + t) * tok_o + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
+            }
         }
         bool pre[kPre];
 #pragma unroll
@@ -348,12 +382,23 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             const int t = base + tid;
             append(t < n_tok && mask[t] != 0, t);
         }
+        if (MODE == kStep) {
+            // a group with no rows that does not write cu_seqlens either is done (whole group, before the barrier)
+            if (m0 >= n && !(h == 0 && m_tile == 0)) return;
+            s = prefix_finish(keep, before_image, lds4);       // kept tokens of the images before this one
+            s = __builtin_amdgcn_readfirstlane(s);
+            if (h == 0 && m_tile == 0 && tid == 0) {
+                if (img == 0) step.cu_seqlens[0] = 0;
+                step.cu_seqlens[img + 1] = s + n;
+            }
+        }
     } else {
         s = cu_seqlens[img];
         n = cu_seqlens[img + 1] - s;
     }
     n = __builtin_amdgcn_readfirstlane(n);
     if (m0 >= n) return;                                       // whole group exits together
+    const int64_t pad0 = (int64_t)img * n_tok;                 // first padded row of the image (kStep)
     // row of the j-th token of this image in q / k / v / o
     auto row_of = [&](int j) -> int64_t { return GATHER ? (int64_t)s + idx_lds[j] : (int64_t)s + j; };
     const bool wave_active = m0 + wave * 16 < n;               // wavefront has at least one real query
@@ -394,6 +439,20 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     issue(0, 0);
 #pragma unroll
     for (int d = 0; d < kRing - 2; ++d) c_next[d] = d + 1 < tiles ? issue(d + 1, d + 1) : 0;
+
+    // ---- kStep: this head's slice of the group's 64 rows of x (two 16-byte units per thread) is requested
+    // now and stored to the packed buffer after the first tile; head 0 also records the source rows
+    uint4 x_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+    if (MODE == kStep) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = m0 + 32 * i + (tid >> 3);
+            if (j < n)
+                x_raw[i] = reinterpret_cast<const uint4*>(step.x + (pad0 + idx_lds[j]) * tok + head_off)[tid & 7];
+        }
+        if (h == 0 && tid < kBM && m0 + tid < n && (int64_t)s + m0 + tid < step.cap_rows)
+            step.gather_idx[s + m0 + tid] = (int32_t)(pad0 + idx_lds[m0 + tid]);
+    }
 
     // ---- Q: this lane's query row, head-dim elements 16g .. 16g+15 (zeros past the sequence end)
     const int q_row = m0 + wave * 16 + col;
@@ -441,7 +500,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         const int c_new = t + kRing - 1 < tiles ? issue(t + kRing - 1, slot_new) : 0;
 #pragma unroll
         for (int d = 0; d + 1 < kRing - 2; ++d) c_next[d] = c_next[d + 1];
-        if (kRing > 2) c_next[kRing - 3] = c_new;
+        if (kRing > 2) c_next[kRing > 2 ? kRing - 3 : 0] = c_new;
         if (wave_active) {
             const int rem = n - t * kBN;
             const uint32_t tile0 = ring0 + slot * 2 * kTileBytes;
@@ -458,10 +517,20 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 }
             }
         }
+        if (MODE == kStep && t == 0) {
+            // the x rows have long arrived: with several tiles the copy drains while the rest is computed
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int j = m0 + 32 * i + (tid >> 3);
+                if (j < n && (int64_t)s + j < step.cap_rows)
+                    reinterpret_cast<uint4*>(step.packed + ((int64_t)s + j) * tok + head_off)[tid & 7] = x_raw[i];
+            }
+        }
         slot = slot == kRing - 1 ? 0 : slot + 1;
     }
 
     // ---- normalise and store: this lane owns d = 16g + 4dt + r of its query
+    const bool row_fits = MODE != kStep || (int64_t)s + q_row < step.cap_rows;
     if (wave_active && q_row < n) {
         const float inv = 1.0f / l_acc[0];
         float out16[16];
@@ -469,15 +538,17 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int r = 0; r < 4; ++r) out16[4 * dt + r] = o_acc[dt][r] * inv;
-        store16(o + row_of(q_row) * tok_o + head_off + 16 * g, out16);
+        if (row_fits) store16(o + row_of(q_row) * tok_o + head_off + 16 * g, out16);
+        if (MODE == kStep)                                     // the same row at its padded position
+            store16(reinterpret_cast<OutT*>(step.out) + (pad0 + idx_lds[q_row]) * tok_o + head_off + 16 * g, out16);
     }
 }
 
-template <typename In, typename OutT, bool GATHER>
+template <typename In, typename OutT, int MODE>
 hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
                         const int32_t* cu_seqlens, const uint8_t* keep, int n_tok, int fill_mode,
                         int B, int max_seqlen, int H, int64_t in_tok, int64_t out_tok, float scale,
-                        hipStream_t stream) {
+                        const StepArgs& step, hipStream_t stream) {
     constexpr int kWaves = kAttnWaves;                         // 16 query rows each
     constexpr int kGroup = 512;                                // pairs per dispatch batch
     const int q_tiles = (max_seqlen + 16 * kWaves - 1) / (16 * kWaves);
@@ -485,28 +556,28 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
     const int pairs8 = (pairs + kXcds - 1) / kXcds * kXcds;
     const int group = pairs8 < kGroup ? pairs8 : kGroup;
     const int batches = (pairs + group - 1) / group;
-    hipLaunchKernelGGL((attn_kernel<In, OutT, GATHER>), dim3(batches * q_tiles * group),
+    hipLaunchKernelGGL((attn_kernel<In, OutT, MODE>), dim3(batches * q_tiles * group),
                        dim3(kAttnThreads), 0, stream,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                        static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, keep, n_tok,
                        fill_mode, H, in_tok, out_tok, pairs, q_tiles, group, fabsf(scale) * kLog2e,
-                       scale < 0.f ? 1 : 0);
+                       scale < 0.f ? 1 : 0, step);
     return hipGetLastError();
 }
 
-template <bool GATHER>
+template <int MODE>
 hipError_t launch_any(const void* q, const void* k, const void* v, void* o, const int32_t* cu_seqlens,
                       const uint8_t* keep, int n_tok, int fill_mode, int B, int max_seqlen, int H,
                       int64_t in_tok, int64_t out_tok, float scale, ragged_dtype in_dt,
-                      ragged_dtype out_dt, hipStream_t stream) {
+                      ragged_dtype out_dt, const StepArgs& step, hipStream_t stream) {
     if (in_dt == RAGGED_F16 && out_dt == RAGGED_F16)
-        return launch_typed<F16, _Float16, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, stream);
+        return launch_typed<F16, _Float16, MODE>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, step, stream);
     if (in_dt == RAGGED_F16 && out_dt == RAGGED_F32)
-        return launch_typed<F16, float, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, stream);
+        return launch_typed<F16, float, MODE>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, step, stream);
     if (in_dt == RAGGED_BF16 && out_dt == RAGGED_BF16)
-        return launch_typed<BF16, __bf16, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, stream);
+        return launch_typed<BF16, __bf16, MODE>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, step, stream);
     if (in_dt == RAGGED_BF16 && out_dt == RAGGED_F32)
-        return launch_typed<BF16, float, GATHER>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, stream);
+        return launch_typed<BF16, float, MODE>(q, k, v, o, cu_seqlens, keep, n_tok, fill_mode, B, max_seqlen, H, in_tok, out_tok, scale, step, stream);
     return hipErrorInvalidValue;
 }
 
@@ -516,8 +587,8 @@ hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, int64_t in_tok,
                        int64_t out_tok, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
                        hipStream_t stream) {
-    return launch_any<false>(q, k, v, o, cu_seqlens, nullptr, 0, 0, B, max_seqlen, H, in_tok, out_tok, scale,
-                             in_dt, out_dt, stream);
+    return launch_any<kPacked>(q, k, v, o, cu_seqlens, nullptr, 0, 0, B, max_seqlen, H, in_tok, out_tok, scale,
+                               in_dt, out_dt, StepArgs{}, stream);
 }
 
 int attn_padded_max_tokens() { return kMaxGatherTokens; }
@@ -526,8 +597,22 @@ hipError_t launch_attn_padded(const void* q, const void* k, const void* v, void*
                               int B, int N, int H, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
                               int fill_mode, hipStream_t stream) {
     const int64_t tok = (int64_t)H * kHeadDim;
-    return launch_any<true>(q, k, v, o, nullptr, keep, N, fill_mode, B, N, H, tok, tok, scale, in_dt, out_dt,
-                            stream);
+    return launch_any<kPadded>(q, k, v, o, nullptr, keep, N, fill_mode, B, N, H, tok, tok, scale, in_dt, out_dt,
+                               StepArgs{}, stream);
+}
+
+hipError_t launch_step(const void* x, const uint8_t* keep, const void* q, const void* k, const void* v,
+                       int B, int N, int H, float scale, ragged_dtype dt, void* packed, int64_t cap_rows,
+                       int32_t* cu_seqlens, int32_t* gather_idx, void* o, void* out, int fill_mode,
+                       hipStream_t stream) {
+    const int64_t tok = (int64_t)H * kHeadDim;
+    const StepArgs step{static_cast<const uint16_t*>(x), static_cast<uint16_t*>(packed),
+                        static_cast<uint16_t*>(out), cu_seqlens, gather_idx, cap_rows};
+    if (dt == RAGGED_F16)
+        return launch_typed<F16, _Float16, kStep>(q, k, v, o, nullptr, keep, N, fill_mode, B, N, H, tok, tok, scale,
+                                                  step, stream);
+    return launch_typed<BF16, __bf16, kStep>(q, k, v, o, nullptr, keep, N, fill_mode, B, N, H, tok, tok, scale,
+                                             step, stream);
 }
 
 }  // namespace ragged

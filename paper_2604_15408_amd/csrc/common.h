@@ -33,6 +33,11 @@ hipError_t launch_repack(const void* packed_in, const uint8_t* keep_rows, const 
                          int32_t* gather_out, hipStream_t stream);
 hipError_t launch_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int C, void* out,
                               hipStream_t stream);
+// pack + attention + unpack of one layer in one launch (x, packed, o, out, q, k, v all of dtype dt)
+hipError_t launch_step(const void* x, const uint8_t* keep, const void* q, const void* k, const void* v,
+                       int B, int N, int H, float scale, ragged_dtype dt, void* packed, int64_t cap_rows,
+                       int32_t* cu_seqlens, int32_t* gather_idx, void* o, void* out, int fill_mode,
+                       hipStream_t stream);
 int attn_padded_max_tokens();
 hipError_t launch_noop(int grid, hipStream_t stream);
 

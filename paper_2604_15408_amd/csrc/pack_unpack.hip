@@ -4,99 +4,10 @@
 // read: every work-group recounts the (tiny) mask prefix it needs from L2, so no grid-wide scan or
 // second kernel is required.
 #include "common.h"
+#include "mask_prefix.h"
 
 namespace ragged {
 namespace {
-
-// Number of nonzero bytes in a 32-bit word.  (b & 0x7f) + 0x7f carries into bit 7 of its own byte
-// exactly when the low 7 bits are nonzero, and never into the next byte.
-__device__ __forceinline__ int nonzero_bytes(uint32_t w) {
-    const uint32_t t = ((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w;
-    return __popc(t & 0x80808080u);
-}
-
-// Sum over the 64 lanes of a wavefront, result in every lane, without going through LDS: four
-// rotations inside each 16-lane row (DPP row_ror 8/4/2/1), then the gfx950 lane-swap instructions
-// across rows.  permlane16_swap(a, b) returns {a.row0,b.row0,a.row2,b.row2} and
-// {a.row1,b.row1,a.row3,b.row3}; permlane32_swap(a, b) returns {a.lo|b.lo} and {a.hi|b.hi}.  The
-// second operand is a copy made through an opaque move so it can never share a register with the
-// first (the instruction swaps its operands in place).
-template <int kCtrl>
-__device__ __forceinline__ int dpp_move(int v) {
-    return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xf, 0xf, true);
-}
-__device__ __forceinline__ int opaque_copy(int x) {
-    int y;
-    asm volatile("v_mov_b32 %0, %1" : "=v"(y) : "v"(x));
-    return y;
-}
-__device__ __forceinline__ int wave_sum(int v) {
-    v += dpp_move<0x128>(v);                                   // row_ror:8
-    v += dpp_move<0x124>(v);                                   // row_ror:4
-    v += dpp_move<0x122>(v);                                   // row_ror:2
-    v += dpp_move<0x121>(v);                                   // row_ror:1
-    const auto a = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)opaque_copy(v), false, false);
-    const unsigned a0 = a[0], a1 = a[1];
-    v = (int)(a0 + a1);
-    const auto b = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)opaque_copy(v), false, false);
-    const unsigned b0 = b[0], b1 = b[1];
-    return (int)(b0 + b1);
-}
-
-// Work-group-wide count of nonzero bytes in base[0, len), in two halves so that a caller can put
-// other memory traffic between them: prefix_issue() starts the loads (first 16 KB of the range into
-// registers), prefix_finish() consumes them, handles any remainder, and reduces over the group.
-// Every thread of the 256-thread group must call both; every thread receives the total.  The bulk
-// is read as aligned 16-byte words; the unaligned head and the tail go byte by byte, so no byte
-// outside [0, len) is ever touched.
-constexpr int kPrefixWords = 4;    // 16-byte words per thread kept in flight: 16 KB per pass of the group
-
-struct PrefixLoads {
-    uint4 w[kPrefixWords];   // words tid + 256*j of the aligned body (zero if absent)
-    uint8_t hb, tb;          // one head byte / one tail byte (zero if absent)
-    int head, body;
-};
-
-__device__ __forceinline__ PrefixLoads prefix_issue(const uint8_t* __restrict__ base, int len) {
-    const int tid = threadIdx.x;
-    PrefixLoads p;
-    const int mis = (int)((uintptr_t)base & 15u);
-    p.head = mis ? 16 - mis : 0;
-    if (p.head > len) p.head = len;
-    p.body = (len - p.head) >> 4;                             // whole 16-byte words
-    const uint4* words = reinterpret_cast<const uint4*>(base + p.head);
-#pragma unroll
-    for (int j = 0; j < kPrefixWords; ++j)
-        p.w[j] = tid + j * kBlockThreads < p.body ? words[tid + j * kBlockThreads] : make_uint4(0u, 0u, 0u, 0u);
-    p.hb = tid < p.head ? base[tid] : (uint8_t)0;
-    const int tail0 = p.head + (p.body << 4);
-    p.tb = tail0 + tid < len ? base[tail0 + tid] : (uint8_t)0;   // fewer than 16 tail bytes
-    return p;
-}
-
-__device__ __forceinline__ int count_word(uint4 v) {
-    return nonzero_bytes(v.x) + nonzero_bytes(v.y) + nonzero_bytes(v.z) + nonzero_bytes(v.w);
-}
-
-__device__ int prefix_finish(const uint8_t* __restrict__ base, const PrefixLoads& p, int* lds4) {
-    const int tid = threadIdx.x;
-    int count = (p.hb != 0) + (p.tb != 0);
-#pragma unroll
-    for (int j = 0; j < kPrefixWords; ++j) count += count_word(p.w[j]);
-    const uint4* words = reinterpret_cast<const uint4*>(base + p.head);
-    for (int w0 = tid + kPrefixWords * kBlockThreads; w0 < p.body; w0 += kPrefixWords * kBlockThreads) {
-        uint4 more[kPrefixWords];                             // all loads of a pass issued before any is used
-#pragma unroll
-        for (int j = 0; j < kPrefixWords; ++j)
-            more[j] = w0 + j * kBlockThreads < p.body ? words[w0 + j * kBlockThreads] : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-        for (int j = 0; j < kPrefixWords; ++j) count += count_word(more[j]);
-    }
-    count = wave_sum(count);
-    if ((tid & (kWaveSize - 1)) == 0) lds4[tid >> 6] = count; // lds4 is used once per kernel
-    __syncthreads();
-    return lds4[0] + lds4[1] + lds4[2] + lds4[3];
-}
 
 // Copy one row of `units` 16-byte words with the 64 lanes of a wavefront (coalesced both ways).
 __device__ __forceinline__ void wave_copy_row(const uint4* __restrict__ src, uint4* __restrict__ dst,

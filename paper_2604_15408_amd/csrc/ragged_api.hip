@@ -7,7 +7,7 @@
 
 namespace {
 
-constexpr int kVersion = 300;  // 0.3.0
+constexpr int kVersion = 400;  // 0.4.0
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_BF16; }
@@ -84,6 +84,24 @@ int ragged_attn_padded(const void* q, const void* k, const void* v, void* o, con
                                                static_cast<hipStream_t>(stream)));
 }
 
+int ragged_pack_attn_unpack(const void* x, const uint8_t* keep, const void* q, const void* k, const void* v,
+                            int B, int N, int H, int D, float scale, ragged_dtype dt, void* packed,
+                            int64_t cap_rows, int32_t* cu_seqlens, int32_t* gather_idx, void* o, void* out,
+                            int fill_mode, void* stream) {
+    if (!x || !keep || !q || !k || !v || !packed || !cu_seqlens || !gather_idx || !o || !out) return RAGGED_ERR_NULL;
+    if (B <= 0 || N <= 0 || H <= 0 || D <= 0 || !rows_fit(B, N)) return RAGGED_ERR_SHAPE;
+    const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)N + 63) / 64);
+    if (groups > (int64_t)INT32_MAX || (int64_t)N * H * D * 2 >= (int64_t)1 << 31) return RAGGED_ERR_SHAPE;
+    if (D != 64 || N > ragged::attn_padded_max_tokens() || !is16bit(dt)) return RAGGED_ERR_UNSUPPORTED;
+    if ((fill_mode != 0 && fill_mode != 1) || !isfinite(scale)) return RAGGED_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(packed) || !aligned16(o) ||
+        !aligned16(out))
+        return RAGGED_ERR_UNSUPPORTED;
+    if (cap_rows < (int64_t)B * N) return RAGGED_ERR_CAPACITY;
+    return from_hip(ragged::launch_step(x, keep, q, k, v, B, N, H, scale, dt, packed, cap_rows, cu_seqlens,
+                                        gather_idx, o, out, fill_mode, static_cast<hipStream_t>(stream)));
+}
+
 int ragged_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlens,
                   const int32_t* gather_idx, int B, int N, int C, ragged_dtype dt,
                   void* out, int fill_mode, void* stream) {
@@ -127,7 +145,7 @@ const char* ragged_status_string(int status) {
         case RAGGED_ERR_NULL: return "a required pointer is NULL";
         case RAGGED_ERR_SHAPE: return "a dimension is non-positive or too large";
         case RAGGED_ERR_UNSUPPORTED: return "unsupported dtype, head dim, alignment, scale or fill mode";
-        case RAGGED_ERR_CAPACITY: return "a row capacity must be at least 1";
+        case RAGGED_ERR_CAPACITY: return "a row capacity is too small";
         case RAGGED_ERR_HIP: return "the HIP runtime refused the launch";
         default: return "unknown";
     }

@@ -36,15 +36,16 @@ class Path:
         dev = "cuda:0"
         B, N, C, H, D = w.B, w.N, w.C, w.H, w.D
         self.T = w.T
-        rows = max(self.T, 1)
+        cap = B * N                                    # row capacity of every packed buffer
         self.x = w.features().to(dev)
         self.keep = w.keep.to(dev)
-        self.packed = torch.zeros(B * N, C, dtype=self.x.dtype, device=dev)
+        self.packed = torch.zeros(cap, C, dtype=self.x.dtype, device=dev)
         self.cu = torch.zeros(B + 1, dtype=torch.int32, device=dev)
-        self.gidx = torch.zeros(B * N, dtype=torch.int32, device=dev)
-        q, k, v = w.qkv(rows)
-        self.q, self.k, self.v = q.to(dev), k.to(dev), v.to(dev)
-        self.o = torch.zeros(rows, H, D, dtype=self.q.dtype, device=dev)
+        self.gidx = torch.zeros(cap, dtype=torch.int32, device=dev)
+        self.q, self.k, self.v = (torch.zeros(cap, H, D, dtype=self.x.dtype, device=dev) for _ in range(3))
+        for dst, src in zip((self.q, self.k, self.v), w.qkv(max(self.T, 1))):
+            dst[: src.shape[0]] = src.to(dev)          # rows past T are never read
+        self.o = torch.zeros(cap, H, D, dtype=self.q.dtype, device=dev)
         self.out = torch.zeros(B, N, C, dtype=self.x.dtype, device=dev)
         torch.cuda.synchronize()
 
@@ -63,6 +64,15 @@ class Path:
         self.pack()
         self.attn()
         self.unpack()
+
+    def one_launch(self):
+        """The same step -- every output of pack, attn and unpack -- as a single launch."""
+        self.b.ragged_pack_attn_unpack(self.x, self.keep, self.q, self.k, self.v, self.packed, self.cu,
+                                       self.gidx, self.o, self.out, self.w.scale, self.fill_mode)
+
+    def prepared_one_launch(self):
+        return self.b.prepare_pack_attn_unpack(self.x, self.keep, self.q, self.k, self.v, self.packed, self.cu,
+                                               self.gidx, self.o, self.out, self.w.scale, self.fill_mode)
 
     def prepared_step(self):
         """The same three launches with arguments marshalled once (binding.Prepared), bound to the
@@ -84,11 +94,17 @@ class Path:
         row = w.C * 2
         sq = sum(n * n for n in w.lengths)
         unpack_bytes = 2 * T * row + 4 * T if self.fill_mode == 0 else T * row + w.B * w.N * row + w.B * w.N
-        return {
+        stages = {
             "pack": {"bytes": w.B * w.N + 2 * T * row + 4 * (w.B + 1) + 4 * T},
             "attn": {"bytes": 4 * T * row, "flops": 4 * w.D * w.H * sq},
             "unpack": {"bytes": unpack_bytes},
         }
+        # the single-launch step moves what the three stages move, except that the attention output
+        # goes straight to both destinations (o is not read back) and gather_idx is not re-read
+        fused = (w.B * w.N + 2 * T * row + 4 * (w.B + 1) + 4 * T) + 4 * T * row + \
+                (T * row if self.fill_mode == 0 else w.B * w.N * row)
+        stages["pack_attn_unpack"] = {"bytes": fused, "flops": stages["attn"]["flops"]}
+        return stages
 
 
 def capture(torch, fn, reps: int = 1):

@@ -2,7 +2,8 @@
 
     python -m paper_2604_15408_amd.suite [--out gpurun_out/suite.jsonl]
 
-Cases: the headline batch; the bf16 pruning-ratio sweep next to a padded baseline of the same shape
+Cases (each with the step issued as three launches and as the single ragged_pack_attn_unpack launch):
+the headline batch; the bf16 pruning-ratio sweep next to a padded baseline of the same shape
 (this library's own attention kernel run with every image at the full N tokens -- the bytes and
 flops a padded dense attention has to spend, with no mask cost added); the 384x384 serving batches;
 the 12-layer progressive-pruning loop captured in ONE HIP graph, both through the padded tensor every
@@ -38,6 +39,9 @@ def case(torch, w, label: str):
     step_graph = wall_steps(torch, g.replay, 300) * 1e6
     lean = p.prepared_step()
     step_lean = wall_steps(torch, lean, 300) * 1e6
+    g_one = capture(torch, p.one_launch, REPLICAS)
+    one_us = event_time_us(torch, g_one.replay, iters=30)[0] / REPLICAS
+    one_wall = wall_steps(torch, p.prepared_one_launch(), 300) * 1e6
     fused = PaddedPath(w, 0)
     g_fused = capture(torch, fused.run, REPLICAS)
     fused_us = event_time_us(torch, g_fused.replay, iters=30)[0] / REPLICAS
@@ -47,8 +51,9 @@ def case(torch, w, label: str):
             "gbs": {k: alg[k]["bytes"] / (us[k] * 1e-6) / 1e9 for k in us},
             "attn_tflops": alg["attn"]["flops"] / (us["attn"] * 1e-6) / 1e12,
             "attn_tokens_per_s": w.T / (us["attn"] * 1e-6),
-            "step_us": {"hipgraph": step_graph, "eager_prepared": step_lean},
-            "step_tokens_per_s": w.T / (min(step_graph, step_lean) * 1e-6)}
+            "step_us": {"hipgraph": step_graph, "eager_prepared": step_lean, "one_launch_prepared": one_wall},
+            "one_launch_kernel_us": one_us,
+            "step_tokens_per_s": w.T / (min(step_graph, step_lean, one_wall) * 1e-6)}
 
 
 def padded_baseline(torch, w):

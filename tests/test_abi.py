@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() >= 300
+    assert binding.version() >= 400
     assert binding.status_string(0) == "ok"
     texts = {binding.status_string(s) for s in range(6)}
     assert len(texts) == 6 and binding.status_string(99) == "unknown"
@@ -126,6 +126,20 @@ def test_cls_extract_validation(lib):
         assert call(**bad) == 2
     for bad in (dict(dt=2), dict(C=20), dict(src=FAKE + 2), dict(out=FAKE + 8)):
         assert call(**bad) == 3
+
+
+def test_pack_attn_unpack_validation(lib):
+    def call(x=FAKE, keep=FAKE, q=FAKE, k=FAKE, v=FAKE, B=2, N=8, H=2, D=64, scale=0.125, dt=0, packed=FAKE, cap=16,
+             cu=FAKE, gi=FAKE, o=FAKE, out=FAKE, fm=0):
+        return lib.ragged_pack_attn_unpack(x, keep, q, k, v, B, N, H, D, scale, dt, packed, cap, cu, gi, o, out, fm, None)
+    for null in ("x", "keep", "q", "k", "v", "packed", "cu", "gi", "o", "out"):
+        assert call(**{null: None}) == 1
+    for bad in (dict(B=0), dict(N=0), dict(H=0), dict(D=-1), dict(B=1 << 20, N=1 << 20)):
+        assert call(**bad) == 2
+    for bad in (dict(D=32), dict(N=1537, cap=1 << 20), dict(dt=2), dict(fm=3), dict(scale=float("nan")),
+                dict(x=FAKE + 2), dict(out=FAKE + 8)):
+        assert call(**bad) == 3
+    assert call(cap=15) == 4
 
 
 def test_noop_validation(lib):

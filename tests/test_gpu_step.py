@@ -1,0 +1,137 @@
+"""GPU parity of ragged_pack_attn_unpack (pack + attention + unpack of one layer in ONE launch): every
+output equals what the three separate entry points produce (bit for bit), and matches the CPU
+oracle's three stages (pack / unpack bit-exact, attention within the attention tolerance)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_15408_amd import binding
+from paper_2604_15408_amd import workloads as wl
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = 2e-3
+
+
+def run_step(w, fill_mode, dtype=torch.float16, seed=0):
+    """Returns the GPU buffers after one fused launch and after the three-launch path on the same inputs."""
+    B, N, C, H, D = w.B, w.N, w.C, w.H, w.D
+    cap = B * N
+    tdt = dtype
+    x = w.features().to(tdt).to(DEV)
+    keep = w.keep.to(DEV)
+    g = torch.Generator().manual_seed(1234 + seed)
+    q, k, v = (torch.randn(cap, H, D, generator=g).to(tdt).to(DEV) for _ in range(3))
+
+    def fresh():
+        return dict(packed=torch.full((cap, C), hp.SENTINEL, dtype=torch.int16, device=DEV).view(tdt),
+                    cu=torch.full((B + 1,), -7, dtype=torch.int32, device=DEV),
+                    gidx=torch.full((cap,), -7, dtype=torch.int32, device=DEV),
+                    o=torch.full((cap, H, D), hp.SENTINEL, dtype=torch.int16, device=DEV).view(tdt),
+                    out=torch.full((B, N, C), hp.SENTINEL, dtype=torch.int16, device=DEV).view(tdt))
+
+    one = fresh()
+    binding.ragged_pack_attn_unpack(x, keep, q, k, v, one["packed"], one["cu"], one["gidx"], one["o"], one["out"],
+                                    w.scale, fill_mode)
+    three = fresh()
+    binding.ragged_pack(x, keep, three["packed"], three["cu"], three["gidx"])
+    binding.ragged_attn(q, k, v, three["o"], three["cu"], N, w.scale)
+    binding.ragged_unpack(three["o"].view(cap, C), keep, three["cu"], three["gidx"], three["out"], fill_mode)
+    torch.cuda.synchronize()
+    return x, (q, k, v), one, three
+
+
+def check(w, fill_mode, dtype=torch.float16, oracle_attn=True):
+    x, (q, k, v), one, three = run_step(w, fill_mode, dtype)
+    for name in ("packed", "cu", "gidx", "o", "out"):
+        a, b = one[name], three[name]
+        if a.dtype in (torch.float16, torch.bfloat16):
+            a, b = a.view(torch.int16), b.view(torch.int16)
+        assert torch.equal(a, b), f"{name} differs from the three-launch path"
+    # oracle: the three stages on the same inputs
+    T = w.T
+    xw = wl.to_words(x.cpu())
+    want_packed, want_cu, want_gidx = oracle.pack(xw, w.keep.numpy())
+    assert np.array_equal(one["cu"].cpu().numpy(), want_cu)
+    assert np.array_equal(one["gidx"][:T].cpu().numpy(), want_gidx)
+    assert np.array_equal(hp.words(one["packed"][:T]), want_packed)
+    assert torch.all(one["gidx"][T:] == -7) and np.all(hp.words(one["packed"][T:]) == hp.SENTINEL)
+    assert np.all(hp.words(one["o"][T:]) == hp.SENTINEL), "o rows past T were written"
+    o_words = hp.words(one["o"][:T]).reshape(T, w.C)
+    init = np.full((w.B, w.N, w.C), hp.SENTINEL, dtype=np.uint16)
+    want_out = oracle.unpack(o_words, w.keep.numpy(), want_cu, w.C, fill_mode, out_init=init)
+    assert np.array_equal(hp.words(one["out"]), want_out)
+    if oracle_attn and T > 0:
+        name = "f16" if dtype == torch.float16 else "bf16"
+        want_o = oracle.attn(wl.to_words(q[:T].cpu()), wl.to_words(k[:T].cpu()), wl.to_words(v[:T].cpu()), want_cu,
+                             w.scale, name, threads=oracle.max_threads())
+        got = one["o"][:T].cpu().to(torch.float64).numpy()
+        bound = TOL + (np.abs(want_o) * 2.0 ** -8 if dtype == torch.bfloat16 else 0.0)
+        assert np.all(np.abs(got - want_o) <= bound), np.max(np.abs(got - want_o))
+
+
+@pytest.mark.parametrize("fill_mode", [0, 1])
+def test_tiny_and_headline(fill_mode):
+    check(wl.tiny(), fill_mode)
+    check(wl.deit_b_pruned(0.2, 32, "f16", 1001), fill_mode)
+
+
+@pytest.mark.parametrize("p,B,dtype", [(1.0, 8, torch.float16), (0.6, 16, torch.bfloat16), (0.1, 32, torch.float16),
+                                       (0.4, 5, torch.bfloat16)])
+def test_pruning_ratios(p, B, dtype):
+    check(wl.deit_b_pruned(p, B, "f16", 77), 1, dtype)
+
+
+def test_serving_384_and_empty_images():
+    check(wl.serving_384(4), 1)
+    B, N = 6, 197
+    keep = wl.keep_bernoulli(B, N, 0.3, 5)
+    keep[0] = 0
+    keep[3] = 0
+    keep[5] = 0
+    keep[5, 196] = 1
+    check(wl.Workload("holes", B, N, 12, 64, "f16", 31, keep), 1)
+    check(wl.Workload("holes", B, N, 12, 64, "f16", 31, keep), 0)
+    check(wl.Workload("nothing", 3, 50, 2, 64, "f16", 32, torch.zeros(3, 50, dtype=torch.uint8)), 1)
+
+
+def test_small_heads_and_odd_sizes():
+    keep = wl.keep_bernoulli(7, 65, 0.5, 9)
+    check(wl.Workload("odd", 7, 65, 1, 64, "f16", 33, keep), 0)
+    keep = wl.keep_bernoulli(3, 1000, 0.2, 10)
+    check(wl.Workload("long", 3, 1000, 3, 64, "f16", 34, keep), 1)
+
+
+def test_graph_replays_match_eager():
+    from paper_2604_15408_amd.harness import capture
+    w = wl.deit_b_pruned(0.3, 8)
+    B, N, C, H, D = w.B, w.N, w.C, w.H, w.D
+    cap = B * N
+    x = w.features().to(DEV)
+    keep = w.keep.to(DEV)
+    g = torch.Generator().manual_seed(5)
+    q, k, v = (torch.randn(cap, H, D, generator=g).to(torch.float16).to(DEV) for _ in range(3))
+    bufs = dict(packed=torch.zeros(cap, C, dtype=torch.float16, device=DEV),
+                cu=torch.zeros(B + 1, dtype=torch.int32, device=DEV),
+                gidx=torch.zeros(cap, dtype=torch.int32, device=DEV),
+                o=torch.zeros(cap, H, D, dtype=torch.float16, device=DEV),
+                out=torch.zeros(B, N, C, dtype=torch.float16, device=DEV))
+
+    def step():
+        binding.ragged_pack_attn_unpack(x, keep, q, k, v, bufs["packed"], bufs["cu"], bufs["gidx"], bufs["o"],
+                                        bufs["out"], w.scale, 1)
+    step()
+    torch.cuda.synchronize()
+    want = {n: t.clone() for n, t in bufs.items()}
+    graph = capture(torch, step)
+    for rep in range(3):
+        for t in bufs.values():
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, t in bufs.items():
+            a, b = (t.view(torch.int16), want[n].view(torch.int16)) if t.dtype == torch.float16 else (t, want[n])
+            assert torch.equal(a, b), n
