@@ -60,6 +60,10 @@ def _load():
         lib.oracle_repack.restype = i64
         lib.oracle_cls_extract.argtypes = [vp, vp, i32, i32, vp]
         lib.oracle_cls_extract.restype = None
+        lib.oracle_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i32]
+        lib.oracle_linear.restype = i32
+        lib.oracle_layernorm.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_double, vp]
+        lib.oracle_layernorm.restype = None
         lib.oracle_max_threads.argtypes = []
         lib.oracle_max_threads.restype = i32
         _lib = lib
@@ -220,3 +224,36 @@ def cls_extract(packed_words, cu_seqlens) -> np.ndarray:
     out = np.full((cu.size - 1, src.shape[1]), 0xFFFF, dtype=np.uint16)
     _load().oracle_cls_extract(_ptr(src), _ptr(cu), cu.size - 1, src.shape[1], _ptr(out))
     return out
+
+
+def linear(x, w, bias=None, residual=None, act: str = "none", dtype: str = "f16", threads: int = 1) -> np.ndarray:
+    """act(x @ w.T + bias) + residual in fp64.  x [M,K], w [N,K], bias [N], residual [M,N] as raw words."""
+    x, w = _words(x, 2), _words(w, 2)
+    M, K = x.shape
+    N = w.shape[0]
+    if w.shape[1] != K:
+        raise ValueError("w must be [N, K] with K = x.shape[1]")
+    b = None if bias is None else _words(bias, 1)
+    r = None if residual is None else _words(residual, 2)
+    if b is not None and b.shape != (N,):
+        raise ValueError("bias must have N entries")
+    if r is not None and r.shape != (M, N):
+        raise ValueError("residual must be [M, N]")
+    y = np.zeros((M, N), dtype=np.float64)
+    rc = _load().oracle_linear(_ptr(x), _ptr(w), None if b is None else _ptr(b), None if r is None else _ptr(r),
+                               _DTYPES[dtype], M, N, K, {"none": 0, "gelu": 1}[act], _ptr(y), int(threads))
+    if rc != 0:
+        raise MemoryError("oracle_linear failed to allocate scratch")
+    return y
+
+
+def layernorm(x, gamma, beta, eps: float, dtype: str = "f16") -> np.ndarray:
+    """Row-wise LayerNorm in fp64 (biased variance).  x [M,C], gamma/beta [C] as raw words."""
+    x = _words(x, 2)
+    M, C = x.shape
+    g, b = _words(gamma, 1), _words(beta, 1)
+    if g.shape != (C,) or b.shape != (C,):
+        raise ValueError("gamma and beta must have C entries")
+    y = np.zeros((M, C), dtype=np.float64)
+    _load().oracle_layernorm(_ptr(x), _ptr(g), _ptr(b), _DTYPES[dtype], M, C, float(eps), _ptr(y))
+    return y

@@ -341,6 +341,66 @@ void oracle_cls_extract(const uint16_t *packed, const int32_t *cu_seqlens, int B
 }
 
 /* Number of OpenMP threads a parallel region would get by default (1 without OpenMP). */
+/*
+ * The linear layers of a packed encoder block (Section 4.3 item 4: after the pruning point the
+ * projections and the MLP run on the packed buffer, one row per kept token).  The paper does not
+ * spell the block out; it is the standard DeiT / ViT pre-norm encoder block:
+ *     h = LayerNorm(x);  qkv = h Wqkv^T + b;  x = x + attn(qkv) Wo^T + bo;
+ *     h = LayerNorm(x);  x = x + GELU(h W1^T + b1) W2^T + b2
+ * with weights stored [out_features][in_features] and the erf form of GELU.
+ *
+ * oracle_linear:  y[m][n] = act( sum_k x[m][k] * w[n][k] + bias[n] ) + residual[m][n]
+ *   act 0 = identity, 1 = GELU(t) = t * (1 + erf(t / sqrt 2)) / 2;  bias and residual may be NULL.
+ *   Everything is decoded to double first; the sum runs over k in ascending order.
+ */
+int oracle_linear(const uint16_t *x, const uint16_t *w, const uint16_t *bias, const uint16_t *residual,
+                  int dtype, int M, int N, int K, int act, double *y, int threads)
+{
+    double *xd = decode_all(x, (int64_t)M * K, dtype);
+    double *wd = decode_all(w, (int64_t)N * K, dtype);
+    if (!xd || !wd) { free(xd); free(wd); return 1; }
+    (void)threads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            double t = 0.0;
+            for (int k = 0; k < K; ++k) t += xd[(int64_t)m * K + k] * wd[(int64_t)n * K + k];
+            if (bias) t += decode(bias[n], dtype);
+            if (act == 1) t = 0.5 * t * (1.0 + erf(t / sqrt(2.0)));
+            if (residual) t += decode(residual[(int64_t)m * N + n], dtype);
+            y[(int64_t)m * N + n] = t;
+        }
+    }
+    free(xd);
+    free(wd);
+    return 0;
+}
+
+/*
+ * oracle_layernorm: per row, y = (x - mean) / sqrt(var + eps) * gamma + beta with the biased
+ * variance (divide by C), the definition used by ViT encoders.
+ */
+void oracle_layernorm(const uint16_t *x, const uint16_t *gamma, const uint16_t *beta, int dtype,
+                      int M, int C, double eps, double *y)
+{
+    for (int m = 0; m < M; ++m) {
+        double mean = 0.0, var = 0.0;
+        for (int c = 0; c < C; ++c) mean += decode(x[(int64_t)m * C + c], dtype);
+        mean /= C;
+        for (int c = 0; c < C; ++c) {
+            double d = decode(x[(int64_t)m * C + c], dtype) - mean;
+            var += d * d;
+        }
+        var /= C;
+        double rstd = 1.0 / sqrt(var + eps);
+        for (int c = 0; c < C; ++c)
+            y[(int64_t)m * C + c] = (decode(x[(int64_t)m * C + c], dtype) - mean) * rstd *
+                                        decode(gamma[c], dtype) + decode(beta[c], dtype);
+    }
+}
+
 int oracle_max_threads(void)
 {
 #ifdef _OPENMP
