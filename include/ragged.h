@@ -204,6 +204,40 @@ int ragged_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int
                        void* out, void* stream);
 
 /*
+ * ragged_linear -- a linear layer over packed rows, for the encoder blocks that Section 4.3 (item 4)
+ * runs on the packed buffer after the pruning point (QKV projection, attention output projection and
+ * the two MLP layers; Section 6, "Implications for pruning research", attributes most of the
+ * realised speed-up of pruning to these, because their cost is linear in the number of kept tokens):
+ *     y[m, n] = act( sum_k x[m, k] * w[n, k] + bias[n] ) + residual[m, n]
+ *
+ *   x        [rows_cap, K]  packed activations (dt)
+ *   w        [N, K]         weights, one output feature per row (dt)
+ *   bias     [N] or NULL    (dt)
+ *   residual [rows_cap, N] or NULL (dt); may be the same buffer as y (each element is read before
+ *                           it is written, by the same thread)
+ *   y        [rows_cap, N]  out (dt); must not overlap x
+ *   rows_dev                NULL, or a DEVICE pointer to the number of valid rows (for example
+ *                           &cu_seqlens[B]); rows processed = min(rows_cap, *rows_dev), read on the
+ *                           device, so the call stays capturable.  Rows beyond are left untouched.
+ *   act                     0: none, 1: GELU in its erf form t * Phi(t)
+ *
+ * Supported: dt = F16 or BF16, N a multiple of 128, K a multiple of 64 and <= 2^22.  MFMA with fp32
+ * accumulation; bias, activation and residual are applied in fp32 before the single rounding to dt.
+ */
+int ragged_linear(const void* x, const void* w, const void* bias, const void* residual, void* y,
+                  int64_t rows_cap, const int32_t* rows_dev, int N, int K, int act, ragged_dtype dt,
+                  void* stream);
+
+/*
+ * ragged_layernorm -- LayerNorm over the feature dimension of packed rows (same blocks as above):
+ *     y[m, :] = (x[m, :] - mean) / sqrt(var + eps) * gamma + beta,   var = biased variance of the row
+ * x, y [rows_cap, C]; gamma, beta [C]; rows_dev as for ragged_linear.  y may be x.
+ * Supported: dt = F16 or BF16, C a multiple of 8 and <= 2048, eps >= 0.  Statistics in fp32.
+ */
+int ragged_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t rows_cap,
+                     const int32_t* rows_dev, int C, float eps, ragged_dtype dt, void* stream);
+
+/*
  * ragged_noop -- enqueue an empty kernel of `grid` work-groups of 256 threads on `stream`.
  * It exists to measure the launch floor that Section 3 ("The Dispatch Overhead") is about,
  * separately from the time the real kernels spend on the GPU.

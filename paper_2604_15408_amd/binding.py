@@ -20,7 +20,7 @@ RAGGED_F16, RAGGED_BF16, RAGGED_F32 = 0, 1, 2
 _DTYPE_CODE = {torch.float16: RAGGED_F16, torch.bfloat16: RAGGED_BF16, torch.float32: RAGGED_F32}
 
 EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_strided", "ragged_attn_padded", "ragged_unpack",
-           "ragged_repack", "ragged_cls_extract", "ragged_pack_attn_unpack", "ragged_noop", "ragged_status_string", "ragged_version")
+           "ragged_repack", "ragged_cls_extract", "ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", "ragged_noop", "ragged_status_string", "ragged_version")
 
 _lib = None
 
@@ -54,6 +54,10 @@ def load() -> ctypes.CDLL:
         lib.ragged_pack_attn_unpack.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, i64, vp, vp,
                                                 vp, vp, i32, vp]
         lib.ragged_pack_attn_unpack.restype = i32
+        lib.ragged_linear.argtypes = [vp, vp, vp, vp, vp, i64, vp, i32, i32, i32, i32, vp]
+        lib.ragged_linear.restype = i32
+        lib.ragged_layernorm.argtypes = [vp, vp, vp, vp, i64, vp, i32, f32, i32, vp]
+        lib.ragged_layernorm.restype = i32
         lib.ragged_attn_padded.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, i32, vp]
         lib.ragged_attn_padded.restype = i32
         lib.ragged_unpack.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
@@ -221,15 +225,62 @@ def ragged_pack_attn_unpack(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o,
                             fill_mode: int = 0, stream=None) -> None:
     """ragged_pack(x, keep) + ragged_attn(q, k, v) + ragged_unpack(o -> out) in one launch; q, k, v,
     o, packed, gather_idx hold cap >= B*N rows."""
-    _check("ragged_pack_attn_unpack", load().ragged_pack_attn_unpack(
+    _check("ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", load().ragged_pack_attn_unpack(
         *_step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream)))
 
 
 def prepare_pack_attn_unpack(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale: float,
                              fill_mode: int = 0, stream=None) -> "Prepared":
-    return Prepared("ragged_pack_attn_unpack", load().ragged_pack_attn_unpack,
+    return Prepared("ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", load().ragged_pack_attn_unpack,
                     _step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream),
                     (x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out))
+
+
+def _rows_dev(rows_dev):
+    """Device pointer to an int32 row count: a 1-element int32 GPU tensor (e.g. cu_seqlens[B:]) or None."""
+    if rows_dev is None:
+        return None
+    if not (isinstance(rows_dev, torch.Tensor) and rows_dev.is_cuda and rows_dev.dtype == torch.int32
+            and rows_dev.numel() >= 1):
+        raise TypeError("rows_dev must be an int32 GPU tensor with at least one element")
+    return rows_dev.data_ptr()
+
+
+def _linear_args(x, w, bias, residual, y, rows_dev, act, stream):
+    rows, K = x.shape
+    N = w.shape[0]
+    return (_dev(x, "x", (torch.float16, torch.bfloat16)), _dev(w, "w", x.dtype, (N, K)),
+            None if bias is None else _dev(bias, "bias", x.dtype, (N,)),
+            None if residual is None else _dev(residual, "residual", x.dtype, (rows, N)),
+            _dev(y, "y", x.dtype, (rows, N)), rows, _rows_dev(rows_dev), N, K, {"none": 0, "gelu": 1}[act],
+            _DTYPE_CODE[x.dtype], _stream(stream))
+
+
+def ragged_linear(x, w, bias, residual, y, rows_dev=None, act: str = "none", stream=None) -> None:
+    """y = act(x @ w.T + bias) + residual over the first min(rows, *rows_dev) rows.  x [rows,K], w [N,K]."""
+    _check("ragged_linear", load().ragged_linear(*_linear_args(x, w, bias, residual, y, rows_dev, act, stream)))
+
+
+def prepare_linear(x, w, bias, residual, y, rows_dev=None, act: str = "none", stream=None) -> "Prepared":
+    return Prepared("ragged_linear", load().ragged_linear, _linear_args(x, w, bias, residual, y, rows_dev, act, stream),
+                    (x, w, bias, residual, y, rows_dev))
+
+
+def _layernorm_args(x, gamma, beta, y, rows_dev, eps, stream):
+    rows, C = x.shape
+    return (_dev(x, "x", (torch.float16, torch.bfloat16)), _dev(gamma, "gamma", x.dtype, (C,)),
+            _dev(beta, "beta", x.dtype, (C,)), _dev(y, "y", x.dtype, (rows, C)), rows, _rows_dev(rows_dev), C,
+            float(eps), _DTYPE_CODE[x.dtype], _stream(stream))
+
+
+def ragged_layernorm(x, gamma, beta, y, rows_dev=None, eps: float = 1e-6, stream=None) -> None:
+    """Row-wise LayerNorm of x [rows,C] into y over the first min(rows, *rows_dev) rows."""
+    _check("ragged_layernorm", load().ragged_layernorm(*_layernorm_args(x, gamma, beta, y, rows_dev, eps, stream)))
+
+
+def prepare_layernorm(x, gamma, beta, y, rows_dev=None, eps: float = 1e-6, stream=None) -> "Prepared":
+    return Prepared("ragged_layernorm", load().ragged_layernorm, _layernorm_args(x, gamma, beta, y, rows_dev, eps, stream),
+                    (x, gamma, beta, y, rows_dev))
 
 
 def ragged_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> None:

@@ -39,13 +39,10 @@
 // together) and P V is two MFMAs; V stays exact.  The path is not MFMA-bound at ViT lengths.
 #include "common.h"
 #include "mask_prefix.h"
+#include "mfma_lds.h"
 
 namespace ragged {
 namespace {
-
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kHeadDim = 64;
 constexpr int kBN = 64;                 // keys per K/V tile
@@ -61,22 +58,6 @@ constexpr int kTileBytes = kBN * kHeadDim * 2;   // one K or one V tile: 8 KB
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazyLog2 = 8.0f;       // probabilities stay below 2^8 between rescales
 constexpr int kMaxGatherTokens = 1536;  // tokens per image the gather-on-load variant can index in LDS
-
-struct F16 {
-    typedef f16x8 vec8;
-    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-    }
-};
-struct BF16 {
-    typedef bf16x8 vec8;
-    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-    }
-};
-
-template <typename V>
-__device__ __forceinline__ V as_vec8(uint4 raw) { return __builtin_bit_cast(V, raw); }
 
 // O^T += V^T P^T for one 32-key block: p[0..7] are this lane's probabilities (fp32).  The row sums
 // of P ride along on the matrix core: with an all-ones A operand every row of the result holds
@@ -151,32 +132,6 @@ __device__ __forceinline__ float quad_max(float x) {
     const unsigned b0 = b[0], b1 = b[1];
     return fmaxf(as_f32(b0), as_f32(b1));
 }
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
-typedef __attribute__((address_space(3))) short4v lds_short4;
-
-__device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
-    const u32x4 w = *reinterpret_cast<const lds_u32x4*>(static_cast<uintptr_t>(addr));
-    return make_uint4(w[0], w[1], w[2], w[3]);
-}
-// transposing 8-byte LDS read (see the header comment)
-__device__ __forceinline__ short4v lds_read_tr(uint32_t addr) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4*>(static_cast<uintptr_t>(addr)));
-}
-
-// One wavefront instruction of the global->LDS load: lane i fetches the 16 bytes at base + voff and
-// the hardware stores them at LDS address lds_dst + 16*i.  The compiler is not told about the LDS
-// write; callers order it against LDS reads with wait_vm<>() and a barrier.
-__device__ __forceinline__ void dma16(uint32_t lds_dst, uint32_t voff, const void* base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_dst), "v"(voff), "s"(base) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vm() {
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
-
 // One K/V tile (already in LDS) against this wavefront's 16 queries: S^T = K Q^T, online-softmax
 // update, O^T += V^T P^T.  NT = 16-key subtiles present in the tile (1..4); MASK: the last subtile may
 // hold keys past the end of the sequence (index >= rem), which are masked out (their LDS rows hold

@@ -38,6 +38,12 @@ hipError_t launch_step(const void* x, const uint8_t* keep, const void* q, const 
                        int B, int N, int H, float scale, ragged_dtype dt, void* packed, int64_t cap_rows,
                        int32_t* cu_seqlens, int32_t* gather_idx, void* o, void* out, int fill_mode,
                        hipStream_t stream);
+// y = act(x w^T + bias) (+ residual) over packed rows; rows = min(rows_cap, *rows_dev) if rows_dev != null
+hipError_t launch_linear(const void* x, const void* w, const void* bias, const void* res, void* y, int rows_cap,
+                         const int32_t* rows_dev, int N, int K, int act, ragged_dtype dt, hipStream_t stream);
+hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int rows_cap,
+                            const int32_t* rows_dev, int C, float eps, ragged_dtype dt, hipStream_t stream);
+int layernorm_max_width();
 int attn_padded_max_tokens();
 hipError_t launch_noop(int grid, hipStream_t stream);
 

@@ -7,7 +7,7 @@
 
 namespace {
 
-constexpr int kVersion = 400;  // 0.4.0
+constexpr int kVersion = 500;  // 0.5.0
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_BF16; }
@@ -132,6 +132,30 @@ int ragged_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int
     if (B <= 0 || C <= 0) return RAGGED_ERR_SHAPE;
     if (!is16bit(dt) || (C & 7) != 0 || !aligned16(packed) || !aligned16(out)) return RAGGED_ERR_UNSUPPORTED;
     return from_hip(ragged::launch_cls_extract(packed, cu_seqlens, B, C, out, static_cast<hipStream_t>(stream)));
+}
+
+int ragged_linear(const void* x, const void* w, const void* bias, const void* residual, void* y,
+                  int64_t rows_cap, const int32_t* rows_dev, int N, int K, int act, ragged_dtype dt,
+                  void* stream) {
+    if (!x || !w || !y) return RAGGED_ERR_NULL;
+    if (rows_cap < 1 || rows_cap > (int64_t)INT32_MAX - 256 || N <= 0 || K <= 0 || K > (1 << 22)) return RAGGED_ERR_SHAPE;
+    if (rows_cap * (int64_t)(N / 128 + 1) > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;    // 32-bit grid
+    if (!is16bit(dt) || (N % 128) != 0 || (K % 64) != 0 || (act != 0 && act != 1)) return RAGGED_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(residual))
+        return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_linear(x, w, bias, residual, y, (int)rows_cap, rows_dev, N, K, act, dt,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+int ragged_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t rows_cap,
+                     const int32_t* rows_dev, int C, float eps, ragged_dtype dt, void* stream) {
+    if (!x || !gamma || !beta || !y) return RAGGED_ERR_NULL;
+    if (rows_cap < 1 || rows_cap > (int64_t)INT32_MAX - 256 || C <= 0) return RAGGED_ERR_SHAPE;
+    if (!is16bit(dt) || (C & 7) != 0 || C > ragged::layernorm_max_width() || !(eps >= 0.f) || !isfinite(eps))
+        return RAGGED_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y)) return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_layernorm(x, gamma, beta, y, (int)rows_cap, rows_dev, C, eps, dt,
+                                             static_cast<hipStream_t>(stream)));
 }
 
 int ragged_noop(int grid, void* stream) {

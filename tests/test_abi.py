@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() >= 400
+    assert binding.version() >= 500
     assert binding.status_string(0) == "ok"
     texts = {binding.status_string(s) for s in range(6)}
     assert len(texts) == 6 and binding.status_string(99) == "unknown"
@@ -140,6 +140,28 @@ def test_pack_attn_unpack_validation(lib):
                 dict(x=FAKE + 2), dict(out=FAKE + 8)):
         assert call(**bad) == 3
     assert call(cap=15) == 4
+
+
+def test_linear_validation(lib):
+    def call(x=FAKE, w=FAKE, b=FAKE, r=None, y=FAKE, rows=16, rd=None, N=128, K=64, act=0, dt=0):
+        return lib.ragged_linear(x, w, b, r, y, rows, rd, N, K, act, dt, None)
+    for null in ("x", "w", "y"):
+        assert call(**{null: None}) == 1
+    for bad in (dict(rows=0), dict(N=0), dict(K=-64), dict(K=(1 << 22) + 64), dict(rows=1 << 31)):
+        assert call(**bad) == 2
+    for bad in (dict(N=192), dict(K=96), dict(act=2), dict(dt=2), dict(x=FAKE + 2), dict(b=FAKE + 8), dict(r=FAKE + 4)):
+        assert call(**bad) == 3
+
+
+def test_layernorm_validation(lib):
+    def call(x=FAKE, g=FAKE, b=FAKE, y=FAKE, rows=16, rd=None, C=768, eps=1e-6, dt=0):
+        return lib.ragged_layernorm(x, g, b, y, rows, rd, C, eps, dt, None)
+    for null in ("x", "g", "b", "y"):
+        assert call(**{null: None}) == 1
+    for bad in (dict(rows=0), dict(C=0)):
+        assert call(**bad) == 2
+    for bad in (dict(C=100), dict(C=4096), dict(eps=-1.0), dict(eps=float("nan")), dict(dt=2), dict(y=FAKE + 8)):
+        assert call(**bad) == 3
 
 
 def test_noop_validation(lib):
