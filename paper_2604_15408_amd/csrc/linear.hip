@@ -5,15 +5,17 @@
 // linear_kernel:  y[m][n] = act( sum_k x[m][k] * w[n][k] + bias[n] ) (+ residual[m][n])
 //   x [rows, K] activations, w [N, K] weights (one output feature per row, so both operands are
 //   contiguous along k, which is how an MFMA lane wants them: 8 consecutive k per 16-byte read).
-//   One work-group computes a 128-token x 128-feature tile; wavefront (wm, wn) owns a 64 x 64
-//   quadrant as 4 x 4 MFMA 16x16x32 tiles with fp32 accumulators.  The product is formed
+//   One work-group computes a tile of tokens x features (128 x 128 with four wavefronts or 256 x 256
+//   with eight); a wavefront owns 64 features x 64 or 128 tokens as 4 x 4 or 4 x 8 MFMA 16x16x32
+//   tiles with fp32 accumulators.  The product is formed
 //   TRANSPOSED (features x tokens: W is the A operand, x the B operand), so that a lane ends up
 //   with, for one token, 16 consecutive output features -- two 16-byte stores per token -- once the
 //   A-operand rows are relabelled: MFMA row m' of feature tile j stands for feature
 //   16*(m'/4) + 4*j + m'%4 of the quadrant.
-//   Operand tiles (128 rows x 64 k = 128-byte rows) are brought into LDS by direct global->LDS
+//   Operand tiles (rows x 64 k = 128-byte rows) are brought into LDS by direct global->LDS
 //   loads, row-major with the chunk swizzle c ^ ((row>>1)&3) that makes every 16-byte operand read
-//   conflict-free, double-buffered: the loads of k-step t+1 are in flight while step t is computed.
+//   conflict-free, in a ring of 2 or 4 stages; a stage is refilled as soon as every wavefront holds
+//   it in registers.
 //   Epilogue in registers: bias, optional GELU (erf form, Abramowitz-Stegun 7.1.26, |error| 1.5e-7,
 //   written so the negative tail does not cancel), optional residual, conversion, store.
 //
@@ -28,11 +30,8 @@
 namespace ragged {
 namespace {
 
-constexpr int kTM = 128;                         // tokens per work-group tile
-constexpr int kTN = 128;                         // output features per work-group tile
 constexpr int kTK = 64;                          // contraction elements per stage: 128-byte LDS rows
-constexpr int kStages = 2;
-constexpr int kOperandBytes = 128 * kTK * 2;     // one operand tile: 16 KB
+constexpr int kBigTileMinGroups = 400;           // use 256 x 256 tiles from this many of them on
 
 // GELU(t) = t * Phi(t) with Phi from erfc(z) ~ poly(u) * exp(-z^2), u = 1 / (1 + p z), z = |t| / sqrt 2.
 __device__ __forceinline__ float gelu_erf(float t) {
@@ -76,14 +75,24 @@ __device__ __forceinline__ void pack16(BF16, const float (&v)[16], uint4& a, uin
 // its own L2); XCD x takes token tiles x, x+8, ... and walks all feature tiles of one token tile
 // before the next, so an activation tile is fetched into one L2 once and the (small) weight matrix
 // is what the XCDs share through the Infinity Cache.
-template <typename In, int ACT, bool HAS_RES>
-__global__ __launch_bounds__(kBlockThreads, 2)
+//
+// Shape of a work-group: WNW x WMW wavefronts, each owning 64 features x 16*MT tokens, i.e. a tile of
+// TN = 64*WNW features x TM = 16*MT*WMW tokens.  The L2 -> LDS traffic per flop falls with the tile
+// size (a 128 x 128 tile needs 1/64 byte per flop, which at MFMA rate is more than the L2s deliver;
+// 256 x 256 halves it), so large problems use 4 x 2 wavefronts of 64 x 128 and small ones, where
+// filling the 256 CUs matters more, 2 x 2 wavefronts of 64 x 64.
+template <typename In, int ACT, bool HAS_RES, int WNW, int WMW, int MT, int STAGES>
+__global__ __launch_bounds__(kWaveSize * WNW * WMW, (WNW * WMW == 4 && STAGES == 2) ? 2 : 1)
 void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
                    const uint16_t* __restrict__ bias, const uint16_t* __restrict__ res,
                    uint16_t* __restrict__ y, int rows_cap, const int32_t* __restrict__ rows_dev, int N, int K,
                    int n_tiles) {
     typedef typename In::vec8 vec8;
-    __shared__ __attribute__((aligned(1024))) uint4 stage_lds[kStages * 2 * kOperandBytes / 16];   // [stage][x | w]
+    constexpr int WAVES = WNW * WMW;
+    constexpr int TN = 64 * WNW, TM = 16 * MT * WMW;
+    constexpr int kXBytes = TM * kTK * 2, kWBytes = TN * kTK * 2;       // operand tiles of one stage
+    constexpr int kStageBytes = kXBytes + kWBytes;
+    __shared__ __attribute__((aligned(1024))) uint4 stage_lds[STAGES * kStageBytes / 16];   // [stage][x | w]
 
     const int xcd = blockIdx.x % kXcds;
     const int local = blockIdx.x / kXcds;
@@ -91,83 +100,117 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     const int n_tile = local % n_tiles;
     int rows = rows_cap;
     if (rows_dev) { const int r = *rows_dev; rows = r < rows ? r : rows; }
-    const int m0 = m_tile * kTM;
+    const int m0 = m_tile * TM;
     if (m0 >= rows) return;                                    // whole group
-    const int n0 = n_tile * kTN;
+    const int n0 = n_tile * TN;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 15;
     const int g = lane >> 4;
-    const int wm = wave & 1, wn = wave >> 1;                   // this wavefront's 64-token / 64-feature quadrant
+    const int wn = wave % WNW, wm = wave / WNW;                // this wavefront's feature / token block
 
-    // ---- global->LDS loads: instruction i (0..3) of this wavefront covers tile rows 32*wave + 8i + lane/8
-    // of x and of w; the lane's LDS slot is position lane%8 of that row = chunk (lane%8) ^ ((row>>1)&3).
+    // ---- global->LDS loads: instruction i of this wavefront covers tile rows 8*(kI*wave + i) + lane/8
+    // of x (kXI instructions) and of w (kWI); the lane's LDS slot is position lane%8 of that row =
+    // chunk (lane%8) ^ ((row>>1)&3).
+    constexpr int kXI = TM / 8 / WAVES, kWI = TN / 8 / WAVES;  // load instructions per wavefront per stage
+    static_assert(TM % (8 * WAVES) == 0 && TN % (8 * WAVES) == 0, "tile rows must split over the wavefronts");
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)stage_lds);
     const uint32_t row_bytes = (uint32_t)K * 2u;
     const uint32_t chunk = 16u * ((lane & 7) ^ ((lane >> 4) & 3));
-    uint32_t voff_x[4], voff_w[4];
+    uint32_t voff_x[kXI], voff_w[kWI];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = 32 * wave + 8 * i + (lane >> 3);
+    for (int i = 0; i < kXI; ++i) {
+        const int r = 8 * (kXI * wave + i) + (lane >> 3);
         const int rx = m0 + r < rows ? r : rows - 1 - m0;     // past the last row: that row again (never stored)
         voff_x[i] = (uint32_t)rx * row_bytes + chunk;
-        voff_w[i] = (uint32_t)r * row_bytes + chunk;
     }
+#pragma unroll
+    for (int i = 0; i < kWI; ++i) voff_w[i] = (uint32_t)(8 * (kWI * wave + i) + (lane >> 3)) * row_bytes + chunk;
     const uint16_t* x_base = x + (int64_t)m0 * K;              // wave-uniform; advances by kTK per step
     const uint16_t* w_base = w + (int64_t)n0 * K;
     auto issue = [&](int kt, int s) {
-        const uint32_t dst = lds0 + s * 2 * kOperandBytes + wave * 4096;
+        const uint32_t dst = lds0 + s * kStageBytes;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            dma16(dst + i * 1024, voff_x[i], x_base + kt * kTK);
-            dma16(dst + i * 1024 + kOperandBytes, voff_w[i], w_base + kt * kTK);
-        }
+        for (int i = 0; i < kXI; ++i) dma16(dst + (kXI * wave + i) * 1024, voff_x[i], x_base + kt * kTK);
+#pragma unroll
+        for (int i = 0; i < kWI; ++i) dma16(dst + kXBytes + (kWI * wave + i) * 1024, voff_w[i], w_base + kt * kTK);
     };
 
     // ---- LDS read addresses inside a stage (x tile first, then w tile)
-    //   x operand (B): row wm*64 + 16*mt + col, chunk 2g + ks
-    const int x_row = wm * 64 + col;
+    //   x operand (B): row wm*16*MT + 16*mt + col, chunk 2g + ks
+    const int x_row = wm * 16 * MT + col;
     const uint32_t x_rel = x_row * 128 + 16 * ((2 * g) ^ ((x_row >> 1) & 3));
     //   w operand (A) of feature tile j: row wn*64 + 16*(col/4) + 4j + col%4, chunk 2g + ks
     uint32_t w_rel[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int w_row = wn * 64 + 16 * (col >> 2) + 4 * j + (col & 3);
-        w_rel[j] = kOperandBytes + w_row * 128 + 16 * ((2 * g) ^ ((w_row >> 1) & 3));
+        w_rel[j] = kXBytes + w_row * 128 + 16 * ((2 * g) ^ ((w_row >> 1) & 3));
     }
 
-    f32x4 acc[4][4];                                           // [feature tile j][token tile mt]
+    f32x4 acc[4][MT];                                          // [feature tile j][token tile mt]
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) acc[j][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < MT; ++mt) acc[j][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // ---- main loop, software-pipelined in half-steps of 32 k.  F0 / F1 hold the operand fragments
+    // of the two halves of a stage; the fragments of the NEXT half are requested from LDS before the
+    // 4*MT MFMAs of the current half are issued, so LDS latency hides behind the matrix core.  The
+    // barrier sits between the two halves: by then a wavefront holds all of stage t in registers,
+    // so the stage's buffer can be refilled (loads for step t+2) a whole step before it is needed.
+    auto read_frags = [&](uint32_t base, int ks, uint4 (&a)[4], uint4 (&b)[MT]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = lds_read16(base + (w_rel[j & 1] ^ (16u * ks)) + (j >> 1) * 1024);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) b[mt] = lds_read16(base + (x_rel ^ (16u * ks)) + mt * 2048);
+    };
+    auto mma = [&](const uint4 (&a)[4], const uint4 (&b)[MT]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[j][mt] = In::mfma(as_vec8<vec8>(a[j]), as_vec8<vec8>(b[mt]), acc[j][mt]);
+    };
     const int ksteps = K / kTK;
-    issue(0, 0);
+    constexpr int kPer = kXI + kWI;         // load instructions of this wavefront per stage
+    // wait until at most `later` stages younger than the wanted one are still in flight
+    auto wait_stage = [&](int later) {
+        if (later <= 0) wait_vm<0>();
+        else if (later == 1) wait_vm<kPer>();
+        else if (later == 2) wait_vm<2 * kPer>();
+        else wait_vm<3 * kPer>();
+    };
+#pragma unroll
+    for (int st = 0; st < STAGES; ++st)
+        if (st < ksteps) issue(st, st);
+    wait_stage((ksteps < STAGES ? ksteps : STAGES) - 1);       // step 0 has landed
+    __syncthreads();
+    uint4 a0[4], b0[MT], a1[4], b1[MT];
+    read_frags(lds0, 0, a0, b0);
+    int buf = 0;                                               // buffer of step kt
     for (int kt = 0; kt < ksteps; ++kt) {
-        const int s = kt & 1;
-        wait_vm<0>();                       // this wavefront's part of step kt has landed
-        __syncthreads();                    // step kt visible; every wavefront is past step kt-1's reads
-        if (kt + 1 < ksteps) issue(kt + 1, s ^ 1);
-        const uint32_t base = lds0 + s * 2 * kOperandBytes;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            uint4 a[4], b[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) a[j] = lds_read16(base + (w_rel[j & 1] ^ (16u * ks)) + (j >> 1) * 1024);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) b[mt] = lds_read16(base + (x_rel ^ (16u * ks)) + mt * 2048);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-                    acc[j][mt] = In::mfma(as_vec8<vec8>(a[j]), as_vec8<vec8>(b[mt]), acc[j][mt]);
+        const int buf_next = buf + 1 == STAGES ? 0 : buf + 1;
+        read_frags(lds0 + buf * kStageBytes, 1, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 1 < ksteps) {
+            const int last_issued = kt + STAGES - 1 < ksteps - 1 ? kt + STAGES - 1 : ksteps - 1;
+            wait_stage(last_issued - (kt + 1));                // step kt+1 has landed
+            __syncthreads();                // ... for every wavefront, and all of them hold step kt in registers
+            if (kt + STAGES < ksteps) issue(kt + STAGES, buf);
+            read_frags(lds0 + buf_next * kStageBytes, 0, a0, b0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        buf = buf_next;
     }
 
-    // ---- epilogue: this lane owns, for token m0 + wm*64 + 16*mt + col, features n_base + 4j + r
+    // ---- epilogue: this lane owns, for token m0 + wm*16*MT + 16*mt + col, features n_base + 4j + r
     const int n_base = n0 + wn * 64 + 16 * g;
     float bias16[16];
 #pragma unroll
@@ -177,8 +220,8 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
         unpack16(In{}, bp[0], bp[1], bias16);
     }
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        const int m = m0 + wm * 64 + 16 * mt + col;
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = m0 + wm * 16 * MT + 16 * mt + col;
         if (m >= rows) continue;
         float v[16];
 #pragma unroll
@@ -287,27 +330,42 @@ void layernorm_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict
     }
 }
 
-template <typename In>
-hipError_t launch_linear_typed(const void* x, const void* w, const void* bias, const void* res, void* y,
+template <typename In, int WNW, int WMW, int MT, int STAGES>
+hipError_t launch_linear_shape(const void* x, const void* w, const void* bias, const void* res, void* y,
                                int rows_cap, const int32_t* rows_dev, int N, int K, int act, hipStream_t stream) {
-    const int n_tiles = N / kTN;
-    const int m_tiles = (rows_cap + kTM - 1) / kTM;
+    constexpr int TN = 64 * WNW, TM = 16 * MT * WMW;
+    const int n_tiles = N / TN;
+    const int m_tiles = (rows_cap + TM - 1) / TM;
     const int m_tiles8 = (m_tiles + kXcds - 1) / kXcds * kXcds;
-    const dim3 grid(m_tiles8 * n_tiles), block(kBlockThreads);
+    const dim3 grid(m_tiles8 * n_tiles), block(kWaveSize * WNW * WMW);
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     const uint16_t* wp = static_cast<const uint16_t*>(w);
     const uint16_t* bp = static_cast<const uint16_t*>(bias);
     const uint16_t* rp = static_cast<const uint16_t*>(res);
     uint16_t* yp = static_cast<uint16_t*>(y);
     if (act == 1 && res)
-        hipLaunchKernelGGL((linear_kernel<In, 1, true>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        hipLaunchKernelGGL((linear_kernel<In, 1, true, WNW, WMW, MT, STAGES>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else if (act == 1)
-        hipLaunchKernelGGL((linear_kernel<In, 1, false>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        hipLaunchKernelGGL((linear_kernel<In, 1, false, WNW, WMW, MT, STAGES>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else if (res)
-        hipLaunchKernelGGL((linear_kernel<In, 0, true>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        hipLaunchKernelGGL((linear_kernel<In, 0, true, WNW, WMW, MT, STAGES>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else
-        hipLaunchKernelGGL((linear_kernel<In, 0, false>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        hipLaunchKernelGGL((linear_kernel<In, 0, false, WNW, WMW, MT, STAGES>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     return hipGetLastError();
+}
+
+// Shape choice from what the host knows (row capacity and N):
+//   * 256 x 256 tiles, two stages, when there are enough of them for well over one round of the
+//     256 CUs (the large tile halves the L2 -> LDS bytes per flop);
+//   * else 128 x 128 tiles with two stages, two work-groups per CU.  (A four-stage ring for grids of
+//     at most one work-group per CU was measured and is slower: 28 against 16 us at 1334 x 2304 x 768.)
+template <typename In>
+hipError_t launch_linear_typed(const void* x, const void* w, const void* bias, const void* res, void* y,
+                               int rows_cap, const int32_t* rows_dev, int N, int K, int act, hipStream_t stream) {
+    const int64_t big_tiles = (int64_t)((rows_cap + 255) / 256) * (N / 256);
+    if (N % 256 == 0 && big_tiles >= kBigTileMinGroups)
+        return launch_linear_shape<In, 4, 2, 8, 2>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
+    return launch_linear_shape<In, 2, 2, 4, 2>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
 }
 
 }  // namespace
