@@ -265,3 +265,64 @@ class StayPackedPipeline:
     @property
     def tokens(self) -> int:
         return sum(w.T for w in self.layers)
+
+
+LN_EPS = 1e-6                    # LayerNorm epsilon of ViT / DeiT encoders
+
+
+class PackedBlocks:
+    """`depth` pre-norm encoder blocks run entirely on the packed buffer (the paper's Section 4.3 item
+    4, "late blocks"): one ragged_pack in front, then per block
+        h = LN(x); qkv = h Wqkv^T + b; a = ragged_attn_strided(qkv); x = x + a Wo^T + b;
+        h = LN(x); x = x + GELU(h W1^T + b1) W2^T + b2
+    (7 launches), and ragged_cls_extract at the end.  Weights are seeded synthetic tensors; every
+    launch takes the packed row count from cu_seqlens[B] on the device, so the loop is capturable
+    and its cost follows the number of kept tokens."""
+
+    def __init__(self, w, depth: int = 8, shared_weights: bool = True):
+        import torch
+        from paper_2604_15408_amd import binding
+        from paper_2604_15408_amd import workloads as wl
+        self.torch, self.b, self.w, self.depth = torch, binding, w, depth
+        dev = "cuda:0"
+        B, N, C, H, D = w.B, w.N, w.C, w.H, w.D
+        cap = B * N
+        self.cap, self.hidden = cap, 4 * C
+        tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
+        self.x_in = w.features().to(dev)
+        self.keep = w.keep.to(dev)
+        self.cu = torch.zeros(B + 1, dtype=torch.int32, device=dev)
+        self.gidx = torch.zeros(cap, dtype=torch.int32, device=dev)
+        self.rows = self.cu[B:]                                     # device row count T
+        sets = 1 if shared_weights else depth
+        self.params = [{k: v.to(dev) for k, v in wl.block_weights(C, 4 * C, w.dtype, 2000 + i).items()}
+                       for i in range(sets)]
+        z = lambda *shape: torch.zeros(*shape, dtype=tdt, device=dev)
+        self.x, self.h, self.qkv, self.a, self.mid = z(cap, C), z(cap, C), z(cap, 3, H, D), z(cap, H, D), z(cap, 4 * C)
+        self.cls = z(B, C)
+        self.launches = 1 + 7 * depth + 1
+        torch.cuda.synchronize()
+
+    def block(self, p):
+        b, w, rows = self.b, self.w, self.rows
+        C = w.C
+        b.ragged_layernorm(self.x, p["ln1_g"], p["ln1_b"], self.h, rows, LN_EPS)
+        b.ragged_linear(self.h, p["w_qkv"], p["b_qkv"], None, self.qkv.view(self.cap, 3 * C), rows)
+        b.ragged_attn_strided(self.qkv[:, 0], self.qkv[:, 1], self.qkv[:, 2], self.a, self.cu, w.N, w.scale)
+        b.ragged_linear(self.a.view(self.cap, C), p["w_o"], p["b_o"], self.x, self.x, rows)
+        b.ragged_layernorm(self.x, p["ln2_g"], p["ln2_b"], self.h, rows, LN_EPS)
+        b.ragged_linear(self.h, p["w_fc1"], p["b_fc1"], None, self.mid, rows, "gelu")
+        b.ragged_linear(self.mid, p["w_fc2"], p["b_fc2"], self.x, self.x, rows)
+
+    def run(self):
+        self.b.ragged_pack(self.x_in, self.keep, self.x, self.cu, self.gidx)
+        for i in range(self.depth):
+            self.block(self.params[i % len(self.params)])
+        self.b.ragged_cls_extract(self.x, self.cu, self.cls)
+
+    def flops(self) -> int:
+        w, T = self.w, self.w.T
+        C = w.C
+        linear = 2 * T * (3 * C * C + C * C + 2 * C * self.hidden)
+        attn = 4 * w.D * w.H * sum(n * n for n in w.lengths)
+        return self.depth * (linear + attn)

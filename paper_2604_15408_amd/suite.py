@@ -7,7 +7,9 @@ the headline batch; the bf16 pruning-ratio sweep next to a padded baseline of th
 (this library's own attention kernel run with every image at the full N tokens -- the bytes and
 flops a padded dense attention has to spend, with no mask cost added); the 384x384 serving batches;
 the 12-layer progressive-pruning loop captured in ONE HIP graph, both through the padded tensor every
-layer (36 kernels) and staying packed (17 kernels).  Kernel times are HIP-event times
+layer (36 kernels) and staying packed (17 kernels); eight packed encoder blocks ("late blocks": LayerNorm,
+QKV projection, ragged attention, output projection, MLP with GELU, residuals) with synthetic weights,
+next to the same blocks over all B*N rows.  Kernel times are HIP-event times
 of a graph holding 20 back-to-back copies of the kernel (divided by 20), so they include the
 in-graph kernel-to-kernel gap that an empty kernel shows separately.
 """
@@ -19,8 +21,8 @@ import os
 import sys
 
 from . import workloads as wl
-from .harness import (REPLICAS, PaddedPath, Path, Pipeline, StayPackedPipeline, capture, event_time_us,
-                      wall_steps)
+from .harness import (REPLICAS, PackedBlocks, PaddedPath, Path, Pipeline, StayPackedPipeline, capture,
+                      event_time_us, wall_steps)
 
 
 def stage_times(torch, p: Path):
@@ -96,9 +98,33 @@ def stay_packed_case(torch):
             "tokens_per_s": pipe.tokens / (wall_graph * 1e-6)}
 
 
+def late_blocks_case(torch, w, label: str, depth: int = 8):
+    """pack + `depth` encoder blocks on the packed rows + CLS read, in one HIP graph, next to the same
+    blocks over all B*N rows (what a padded pipeline computes)."""
+    def timed(workload):
+        pb = PackedBlocks(workload, depth)
+        pb.run()
+        torch.cuda.synchronize()
+        g = capture(torch, pb.run)
+        gpu_us = event_time_us(torch, g.replay, iters=20)[0]
+        return pb, gpu_us, wall_steps(torch, g.replay, 50) * 1e6
+    pb, gpu_us, wall_us = timed(w)
+    full = wl.deit_b_pruned(1.0, w.B, w.dtype, w.seed) if w.N == 197 else None
+    rec = {"case": label, "workload": w.name, "B": w.B, "N": w.N, "T": w.T, "depth": depth,
+           "kernels_in_graph": pb.launches, "graph_gpu_us": gpu_us, "graph_wall_us": wall_us,
+           "us_per_block": gpu_us / depth, "tflops": pb.flops() / gpu_us / 1e6,
+           "tokens_per_s": w.T * depth / (wall_us * 1e-6), "images_per_s_through_late_blocks": w.B / (wall_us * 1e-6)}
+    if full is not None and full.T != w.T:
+        _, pad_us, _ = timed(full)
+        rec["padded_graph_gpu_us"] = pad_us
+        rec["speedup_vs_padded"] = pad_us / gpu_us
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default=None)
+    ap.add_argument("--only", default=None, help="run only the cases whose name starts with this (e.g. late_blocks)")
     args = ap.parse_args()
     import torch
     from . import binding
@@ -111,19 +137,30 @@ def main():
         lines.append(rec)
         print(json.dumps(rec), flush=True)
 
-    emit(case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "headline"))
-    pad_us = None
-    for w in wl.sweep():
-        rec = case(torch, w, "sweep")
-        if pad_us is None:
-            pad_us = padded_baseline(torch, w)
-        rec["padded_attn_us"] = pad_us
-        rec["attn_speedup_vs_padded"] = pad_us / rec["kernel_us"]["attn"]
-        emit(rec)
-    for B in (1, 2, 4, 32):
-        emit(case(torch, wl.serving_384(B), "serving_384"))
-    emit(pipeline_case(torch))
-    emit(stay_packed_case(torch))
+    def want(name):
+        return args.only is None or name.startswith(args.only)
+
+    if want("headline"):
+        emit(case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "headline"))
+    if want("sweep"):
+        pad_us = None
+        for w in wl.sweep():
+            rec = case(torch, w, "sweep")
+            if pad_us is None:
+                pad_us = padded_baseline(torch, w)
+            rec["padded_attn_us"] = pad_us
+            rec["attn_speedup_vs_padded"] = pad_us / rec["kernel_us"]["attn"]
+            emit(rec)
+    if want("serving_384"):
+        for B in (1, 2, 4, 32):
+            emit(case(torch, wl.serving_384(B), "serving_384"))
+    if want("pipeline"):
+        emit(pipeline_case(torch))
+        emit(stay_packed_case(torch))
+    if want("late_blocks"):
+        emit(late_blocks_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "late_blocks_headline"))
+        emit(late_blocks_case(torch, wl.deit_b_pruned(0.5, 8, "f16", 1005), "late_blocks_bs8_keep0.5"))
+        emit(late_blocks_case(torch, wl.deit_b_pruned(1.0, 64, "f16", 1006), "late_blocks_bs64_dense"))
     if args.out:
         os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
         with open(args.out, "w") as f:

@@ -170,3 +170,23 @@ def pipeline(seed: int = 1004) -> List[Workload]:
     return [Workload(f"pipeline_layer{l + 1}", 64, 197, 12, 64, "f16", seed + l + 1, m,
                      note="progressive keep 0.7 at layers 3/6/9")
             for l, m in enumerate(masks)]
+
+
+def block_weights(C: int = 768, hidden: int = 3072, dtype: str = "f16", seed: int = 2000):
+    """Seeded synthetic parameters of one pre-norm encoder block (there are no trained weights here):
+    weights [out_features, in_features] ~ N(0, 1/in_features), biases ~ N(0, 0.02^2), LayerNorm gains
+    1 + N(0, 0.1^2) and shifts N(0, 0.1^2).  Returned as CPU tensors of the activation dtype."""
+    g = torch.Generator().manual_seed(seed)
+    tdt = _TORCH_DTYPE[dtype]
+
+    def rnd(*shape, scale=1.0, shift=0.0):
+        return (torch.randn(*shape, generator=g, dtype=torch.float32) * scale + shift).to(tdt)
+
+    return {
+        "ln1_g": rnd(C, scale=0.1, shift=1.0), "ln1_b": rnd(C, scale=0.1),
+        "w_qkv": rnd(3 * C, C, scale=C ** -0.5), "b_qkv": rnd(3 * C, scale=0.02),
+        "w_o": rnd(C, C, scale=C ** -0.5), "b_o": rnd(C, scale=0.02),
+        "ln2_g": rnd(C, scale=0.1, shift=1.0), "ln2_b": rnd(C, scale=0.1),
+        "w_fc1": rnd(hidden, C, scale=C ** -0.5), "b_fc1": rnd(hidden, scale=0.02),
+        "w_fc2": rnd(C, hidden, scale=hidden ** -0.5), "b_fc2": rnd(C, scale=0.02),
+    }

@@ -123,3 +123,83 @@ def test_layernorm_rows_and_in_place():
     assert torch.equal(got[17:], x[17:])
     want = oracle.layernorm(wl.to_words(x[:17]), wl.to_words(g), wl.to_words(b), 1e-6)
     assert np.all(np.abs(got[:17].to(torch.float64).numpy() - want) <= 2.0 ** -10 * np.abs(want) + 2e-5)
+
+
+def test_packed_block_stage_by_stage_against_the_oracle():
+    """One encoder block on packed rows: every launch is checked against the oracle applied to the GPU's
+    own input of that launch (so rounding of intermediate activations is not compared twice)."""
+    from paper_2604_15408_amd.harness import LN_EPS, PackedBlocks
+    from tests import helpers as hp
+    w = wl.deit_b_pruned(0.35, B=3, dtype="f16", seed=91)
+    pb = PackedBlocks(w, depth=1)
+    T, C, H, D = w.T, w.C, w.H, w.D
+    p = {k: wl.to_words(v.cpu()) for k, v in pb.params[0].items()}
+    words = lambda t: wl.to_words(t[:T].reshape(T, -1).cpu())
+    f64 = lambda t: t[:T].reshape(T, -1).cpu().to(torch.float64).numpy()
+    threads = oracle.max_threads()
+
+    def close(got, want, S=None, rel=2.0 ** -10):
+        bound = rel * np.abs(want) + 1e-5 * (1 + np.abs(want)) + (0 if S is None else 2.0 ** -15 * S)
+        assert np.all(np.abs(got - want) <= bound), float(np.max(np.abs(got - want) / bound))
+
+    def lin(xin, wk, bk, res=None, act="none"):
+        want = oracle.linear(xin, p[wk], p[bk], res, act, "f16", threads=threads)
+        S = oracle.linear(wl.to_words(torch.from_numpy(xin.view(np.float16)).abs()),
+                          wl.to_words(torch.from_numpy(p[wk].view(np.float16)).abs()), dtype="f16", threads=threads)
+        return want, S
+
+    b = pb.b
+    b.ragged_pack(pb.x_in, pb.keep, pb.x, pb.cu, pb.gidx)
+    torch.cuda.synchronize()
+    assert int(pb.cu[-1]) == T
+    x0 = words(pb.x)
+    b.ragged_layernorm(pb.x, pb.params[0]["ln1_g"], pb.params[0]["ln1_b"], pb.h, pb.rows, LN_EPS)
+    torch.cuda.synchronize()
+    close(f64(pb.h), oracle.layernorm(x0, p["ln1_g"], p["ln1_b"], LN_EPS))
+    h1 = words(pb.h)
+    b.ragged_linear(pb.h, pb.params[0]["w_qkv"], pb.params[0]["b_qkv"], None, pb.qkv.view(pb.cap, 3 * C), pb.rows)
+    torch.cuda.synchronize()
+    close(f64(pb.qkv), *lin(h1, "w_qkv", "b_qkv"))
+    qkv = pb.qkv[:T].cpu()
+    b.ragged_attn_strided(pb.qkv[:, 0], pb.qkv[:, 1], pb.qkv[:, 2], pb.a, pb.cu, w.N, w.scale)
+    torch.cuda.synchronize()
+    want_a = oracle.attn(wl.to_words(qkv[:, 0].contiguous()), wl.to_words(qkv[:, 1].contiguous()),
+                         wl.to_words(qkv[:, 2].contiguous()), hp.cu_from_lengths(w.lengths), w.scale, "f16", threads=threads)
+    got_a = pb.a[:T].cpu().to(torch.float64).numpy()
+    vmax = float(qkv[:, 2].abs().max())
+    assert np.max(np.abs(got_a - want_a)) <= 2e-3 * max(1.0, vmax)      # the attention bar, scaled by |v|
+    a_w = words(pb.a)
+    b.ragged_linear(pb.a.view(pb.cap, C), pb.params[0]["w_o"], pb.params[0]["b_o"], pb.x, pb.x, pb.rows)
+    torch.cuda.synchronize()
+    want, S = lin(a_w, "w_o", "b_o", x0)
+    close(f64(pb.x), want, S)
+    x1 = words(pb.x)
+    b.ragged_layernorm(pb.x, pb.params[0]["ln2_g"], pb.params[0]["ln2_b"], pb.h, pb.rows, LN_EPS)
+    torch.cuda.synchronize()
+    close(f64(pb.h), oracle.layernorm(x1, p["ln2_g"], p["ln2_b"], LN_EPS))
+    h2 = words(pb.h)
+    b.ragged_linear(pb.h, pb.params[0]["w_fc1"], pb.params[0]["b_fc1"], None, pb.mid, pb.rows, "gelu")
+    torch.cuda.synchronize()
+    want, S = lin(h2, "w_fc1", "b_fc1", None, "gelu")
+    close(f64(pb.mid), want, S)
+    mid = words(pb.mid)
+    b.ragged_linear(pb.mid, pb.params[0]["w_fc2"], pb.params[0]["b_fc2"], pb.x, pb.x, pb.rows)
+    torch.cuda.synchronize()
+    want, S = lin(mid, "w_fc2", "b_fc2", x1)
+    close(f64(pb.x), want, S)
+    # rows past T of every buffer were never written
+    assert not pb.x[T:].any() and not pb.mid[T:].any() and not pb.qkv[T:].any()
+    # the whole loop (pack + block + CLS) in a graph reproduces the eager result
+    from paper_2604_15408_amd.harness import capture
+    pb.run()
+    torch.cuda.synchronize()
+    want_x, want_cls = pb.x.clone(), pb.cls.clone()
+    g = capture(torch, pb.run)
+    for _ in range(2):
+        pb.x.zero_(); pb.cls.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(pb.x.view(torch.int16), want_x.view(torch.int16))
+        assert torch.equal(pb.cls.view(torch.int16), want_cls.view(torch.int16))
+    assert np.array_equal(wl.to_words(pb.cls.cpu()), oracle.cls_extract(words(pb.x), hp.cu_from_lengths(w.lengths)))
