@@ -26,6 +26,10 @@
  *   - unpack (named but not described by the paper) is the inverse scatter of pack; dropped rows
  *     are either left untouched (fill_mode 0) or written with +0 words (fill_mode 1).
  *
+ * Also here, for the parts built around the path: attention on the padded layout, packed-to-packed
+ * re-pack, CLS extraction, and the linear layer / LayerNorm of the encoder blocks that run on
+ * packed rows -- each the plain definition, each with its own pins in tests/test_oracle_*.py.
+ *
  * Parity pins (tests/test_oracle_*.py): brute-force padded+masked attention written separately in
  * NumPy; torch's float64 scaled_dot_product_attention for one sequence; closed forms (n=1,
  * scale=0 -> mean of V, identical V rows, two-token sigmoid case, large-scale argmax limit);
