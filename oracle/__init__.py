@@ -64,6 +64,10 @@ def _load():
         lib.oracle_linear.restype = i32
         lib.oracle_layernorm.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_double, vp]
         lib.oracle_layernorm.restype = None
+        lib.oracle_scores_l2.argtypes = [vp, i32, i64, i32, vp]
+        lib.oracle_scores_l2.restype = None
+        lib.oracle_keep_topk.argtypes = [vp, i32, i32, i32, vp]
+        lib.oracle_keep_topk.restype = None
         lib.oracle_max_threads.argtypes = []
         lib.oracle_max_threads.restype = i32
         _lib = lib
@@ -257,3 +261,23 @@ def layernorm(x, gamma, beta, eps: float, dtype: str = "f16") -> np.ndarray:
     y = np.zeros((M, C), dtype=np.float64)
     _load().oracle_layernorm(_ptr(x), _ptr(g), _ptr(b), _DTYPES[dtype], M, C, float(eps), _ptr(y))
     return y
+
+
+def scores_l2(x_words, dtype: str = "f16") -> np.ndarray:
+    """Squared l2 norm of every token row: x [B,N,C] words -> [B,N] float64."""
+    x = _words(x_words, 3)
+    B, N, C = x.shape
+    out = np.zeros((B, N), dtype=np.float64)
+    _load().oracle_scores_l2(_ptr(x), _DTYPES[dtype], B * N, C, _ptr(out))
+    return out
+
+
+def keep_topk(scores, k: int) -> np.ndarray:
+    """Per image: token 0 plus the k-1 highest-scoring other tokens (ties: lower position first) -> [B,N] uint8."""
+    s = np.ascontiguousarray(scores, dtype=np.float64)
+    if s.ndim != 2 or k < 1:
+        raise ValueError("scores must be [B, N] and k >= 1")
+    B, N = s.shape
+    keep = np.zeros((B, N), dtype=np.uint8)
+    _load().oracle_keep_topk(_ptr(s), B, N, int(k), _ptr(keep))
+    return keep

@@ -405,6 +405,45 @@ void oracle_layernorm(const uint16_t *x, const uint16_t *gamma, const uint16_t *
     }
 }
 
+/*
+ * A keep-mask producer (Section 5, "Experiments": the timings prune with a threshold on the l2 norm
+ * of the token features at a fixed ratio; the paper does not define the method further, and
+ * Section 4.3 item 2 accepts any method that yields a per-token keep mask).  Reading taken here:
+ * a token's score is the squared l2 norm of its feature row; per image the class token (position 0)
+ * is always kept and, of the remaining tokens, the k-1 with the largest score; equal scores are
+ * ordered by position (lower first).  k >= N keeps everything.
+ *
+ * oracle_scores_l2: score[i][t] = sum_c x[i][t][c]^2 in double, c ascending.
+ */
+void oracle_scores_l2(const uint16_t *x, int dtype, int64_t rows, int C, double *scores)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        double acc = 0.0;
+        for (int c = 0; c < C; ++c) {
+            double v = decode(x[r * C + c], dtype);
+            acc += v * v;
+        }
+        scores[r] = acc;
+    }
+}
+
+/*
+ * oracle_keep_topk: keep[i][0] = 1; for t >= 1, keep[i][t] = 1 iff fewer than k-1 tokens u >= 1 of the
+ * same image come before t in the order (score descending, position ascending).  Plain O(N^2) count.
+ */
+void oracle_keep_topk(const double *scores, int B, int N, int k, uint8_t *keep)
+{
+    for (int i = 0; i < B; ++i) {
+        const double *s = scores + (int64_t)i * N;
+        for (int t = 0; t < N; ++t) {
+            int before = 0;
+            for (int u = 1; u < N; ++u)
+                if (u != t && (s[u] > s[t] || (s[u] == s[t] && u < t))) ++before;
+            keep[(int64_t)i * N + t] = (uint8_t)((t == 0 || before < k - 1) ? 1 : 0);
+        }
+    }
+}
+
 int oracle_max_threads(void)
 {
 #ifdef _OPENMP
