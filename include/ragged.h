@@ -238,6 +238,27 @@ int ragged_layernorm(const void* x, const void* gamma, const void* beta, void* y
                      const int32_t* rows_dev, int C, float eps, ragged_dtype dt, void* stream);
 
 /*
+ * ragged_token_scores_l2 and ragged_keep_topk -- a keep-mask producer in front of ragged_pack.  The
+ * pipeline takes its keep mask from any pruning method (Section 4.3 item 2); the paper's timings use
+ * a threshold on the l2 norm of the token features at a fixed ratio (Section 5) and leave the method
+ * undefined.  The definition taken here: score = squared l2 norm of the token's feature row; per
+ * image the class token (position 0) is kept and, of the other tokens, the k-1 with the largest
+ * score, equal scores ordered by position (lower first).  Every image then keeps min(k, N) tokens,
+ * the uniform-length setting of the paper's kernel-latency tables.  ragged_keep_topk is independent
+ * of how the scores were made (attention-based scores of other pruning methods fit as well).
+ *
+ *   x      [rows, C]   token features (dt), rows = B*N
+ *   scores [rows]      out / in: fp64, 8-byte aligned.  Accumulated in fp64 (squares of 16-bit values
+ *                      are exact there), so ranking does not depend on the summation order except
+ *                      between scores that agree to the last bit of a rounded sum
+ *   keep   [B, N]      out: 1 = keep, 0 = drop
+ *
+ * Supported: dt = F16 or BF16, C a multiple of 8; N <= 1536, k >= 1 (k >= N keeps everything).
+ */
+int ragged_token_scores_l2(const void* x, int64_t rows, int C, ragged_dtype dt, double* scores, void* stream);
+int ragged_keep_topk(const double* scores, int B, int N, int k, uint8_t* keep, void* stream);
+
+/*
  * ragged_noop -- enqueue an empty kernel of `grid` work-groups of 256 threads on `stream`.
  * It exists to measure the launch floor that Section 3 ("The Dispatch Overhead") is about,
  * separately from the time the real kernels spend on the GPU.

@@ -20,7 +20,7 @@ RAGGED_F16, RAGGED_BF16, RAGGED_F32 = 0, 1, 2
 _DTYPE_CODE = {torch.float16: RAGGED_F16, torch.bfloat16: RAGGED_BF16, torch.float32: RAGGED_F32}
 
 EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_strided", "ragged_attn_padded", "ragged_unpack",
-           "ragged_repack", "ragged_cls_extract", "ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", "ragged_noop", "ragged_status_string", "ragged_version")
+           "ragged_repack", "ragged_cls_extract", "ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", "ragged_token_scores_l2", "ragged_keep_topk", "ragged_noop", "ragged_status_string", "ragged_version")
 
 _lib = None
 
@@ -58,6 +58,10 @@ def load() -> ctypes.CDLL:
         lib.ragged_linear.restype = i32
         lib.ragged_layernorm.argtypes = [vp, vp, vp, vp, i64, vp, i32, f32, i32, vp]
         lib.ragged_layernorm.restype = i32
+        lib.ragged_token_scores_l2.argtypes = [vp, i64, i32, i32, vp, vp]
+        lib.ragged_token_scores_l2.restype = i32
+        lib.ragged_keep_topk.argtypes = [vp, i32, i32, i32, vp, vp]
+        lib.ragged_keep_topk.restype = i32
         lib.ragged_attn_padded.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, i32, vp]
         lib.ragged_attn_padded.restype = i32
         lib.ragged_unpack.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
@@ -225,13 +229,13 @@ def ragged_pack_attn_unpack(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o,
                             fill_mode: int = 0, stream=None) -> None:
     """ragged_pack(x, keep) + ragged_attn(q, k, v) + ragged_unpack(o -> out) in one launch; q, k, v,
     o, packed, gather_idx hold cap >= B*N rows."""
-    _check("ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", load().ragged_pack_attn_unpack(
+    _check("ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", "ragged_token_scores_l2", "ragged_keep_topk", load().ragged_pack_attn_unpack(
         *_step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream)))
 
 
 def prepare_pack_attn_unpack(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale: float,
                              fill_mode: int = 0, stream=None) -> "Prepared":
-    return Prepared("ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", load().ragged_pack_attn_unpack,
+    return Prepared("ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", "ragged_token_scores_l2", "ragged_keep_topk", load().ragged_pack_attn_unpack,
                     _step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream),
                     (x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out))
 
@@ -281,6 +285,22 @@ def ragged_layernorm(x, gamma, beta, y, rows_dev=None, eps: float = 1e-6, stream
 def prepare_layernorm(x, gamma, beta, y, rows_dev=None, eps: float = 1e-6, stream=None) -> "Prepared":
     return Prepared("ragged_layernorm", load().ragged_layernorm, _layernorm_args(x, gamma, beta, y, rows_dev, eps, stream),
                     (x, gamma, beta, y, rows_dev))
+
+
+def ragged_token_scores_l2(x, scores, stream=None) -> None:
+    """scores[b, t] = squared l2 norm of x[b, t, :] (fp64).  x [B,N,C] f16/bf16, scores [B,N] float64."""
+    B, N, C = x.shape
+    _check("ragged_token_scores_l2", load().ragged_token_scores_l2(
+        _dev(x, "x", (torch.float16, torch.bfloat16)), B * N, C, _DTYPE_CODE[x.dtype],
+        _dev(scores, "scores", torch.float64, (B, N)), _stream(stream)))
+
+
+def ragged_keep_topk(scores, k: int, keep, stream=None) -> None:
+    """keep[b] = token 0 plus the k-1 highest-scoring other tokens of image b (ties: lower position)."""
+    B, N = scores.shape
+    _check("ragged_keep_topk", load().ragged_keep_topk(
+        _dev(scores, "scores", torch.float64), B, N, int(k), _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)),
+        _stream(stream)))
 
 
 def ragged_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> None:

@@ -15,7 +15,7 @@ ROOT = PKG.parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libragged_hip.so"
 BUILD_DIR = PKG / "_build"
-SOURCES = ["ragged_api.hip", "pack_unpack.hip", "attn.hip", "linear.hip"]
+SOURCES = ["ragged_api.hip", "pack_unpack.hip", "attn.hip", "linear.hip", "mask.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

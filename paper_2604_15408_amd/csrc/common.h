@@ -44,6 +44,10 @@ hipError_t launch_linear(const void* x, const void* w, const void* bias, const v
 hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int rows_cap,
                             const int32_t* rows_dev, int C, float eps, ragged_dtype dt, hipStream_t stream);
 int layernorm_max_width();
+hipError_t launch_token_scores_l2(const void* x, int64_t rows, int C, ragged_dtype dt, double* scores,
+                                  hipStream_t stream);
+hipError_t launch_keep_topk(const double* scores, int B, int N, int k, uint8_t* keep, hipStream_t stream);
+int keep_topk_max_tokens();
 int attn_padded_max_tokens();
 hipError_t launch_noop(int grid, hipStream_t stream);
 

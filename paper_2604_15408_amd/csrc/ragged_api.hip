@@ -7,7 +7,7 @@
 
 namespace {
 
-constexpr int kVersion = 500;  // 0.5.0
+constexpr int kVersion = 600;  // 0.6.0
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_BF16; }
@@ -156,6 +156,22 @@ int ragged_layernorm(const void* x, const void* gamma, const void* beta, void* y
     if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y)) return RAGGED_ERR_UNSUPPORTED;
     return from_hip(ragged::launch_layernorm(x, gamma, beta, y, (int)rows_cap, rows_dev, C, eps, dt,
                                              static_cast<hipStream_t>(stream)));
+}
+
+int ragged_token_scores_l2(const void* x, int64_t rows, int C, ragged_dtype dt, double* scores, void* stream) {
+    if (!x || !scores) return RAGGED_ERR_NULL;
+    if (rows < 1 || rows > (int64_t)INT32_MAX || C <= 0) return RAGGED_ERR_SHAPE;
+    if (!is16bit(dt) || (C & 7) != 0 || !aligned16(x) || (reinterpret_cast<uintptr_t>(scores) & 7u) != 0)
+        return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_token_scores_l2(x, rows, C, dt, scores, static_cast<hipStream_t>(stream)));
+}
+
+int ragged_keep_topk(const double* scores, int B, int N, int k, uint8_t* keep, void* stream) {
+    if (!scores || !keep) return RAGGED_ERR_NULL;
+    if (B <= 0 || N <= 0 || k < 1 || !rows_fit(B, N)) return RAGGED_ERR_SHAPE;
+    if (N > ragged::keep_topk_max_tokens() || (reinterpret_cast<uintptr_t>(scores) & 7u) != 0)
+        return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_keep_topk(scores, B, N, k, keep, static_cast<hipStream_t>(stream)));
 }
 
 int ragged_noop(int grid, void* stream) {

@@ -23,7 +23,7 @@ def lib():
 def declared_functions():
     text = (ROOT / "include" / "ragged.h").read_text()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ragged_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(ragged_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() >= 500
+    assert binding.version() >= 600
     assert binding.status_string(0) == "ok"
     texts = {binding.status_string(s) for s in range(6)}
     assert len(texts) == 6 and binding.status_string(99) == "unknown"
@@ -162,6 +162,21 @@ def test_layernorm_validation(lib):
         assert call(**bad) == 2
     for bad in (dict(C=100), dict(C=4096), dict(eps=-1.0), dict(eps=float("nan")), dict(dt=2), dict(y=FAKE + 8)):
         assert call(**bad) == 3
+
+
+def test_mask_producer_validation(lib):
+    assert lib.ragged_token_scores_l2(None, 8, 64, 0, FAKE, None) == 1
+    assert lib.ragged_token_scores_l2(FAKE, 8, 64, 0, None, None) == 1
+    assert lib.ragged_token_scores_l2(FAKE, 0, 64, 0, FAKE, None) == 2
+    assert lib.ragged_token_scores_l2(FAKE, 8, 0, 0, FAKE, None) == 2
+    for bad in ((8, 12, 0, FAKE), (8, 64, 2, FAKE), (8, 64, 0, FAKE + 4)):
+        assert lib.ragged_token_scores_l2(FAKE, bad[0], bad[1], bad[2], bad[3], None) == 3
+    assert lib.ragged_token_scores_l2(FAKE + 8, 8, 64, 0, FAKE, None) == 3
+    assert lib.ragged_keep_topk(None, 2, 8, 3, FAKE, None) == 1 and lib.ragged_keep_topk(FAKE, 2, 8, 3, None, None) == 1
+    for bad in ((0, 8, 3), (2, 0, 3), (2, 8, 0), (1 << 20, 1 << 20, 3)):
+        assert lib.ragged_keep_topk(FAKE, bad[0], bad[1], bad[2], FAKE, None) == 2
+    assert lib.ragged_keep_topk(FAKE, 2, 1537, 3, FAKE, None) == 3
+    assert lib.ragged_keep_topk(FAKE + 4, 2, 8, 3, FAKE, None) == 3
 
 
 def test_noop_validation(lib):
