@@ -20,7 +20,8 @@ RAGGED_F16, RAGGED_BF16, RAGGED_F32 = 0, 1, 2
 _DTYPE_CODE = {torch.float16: RAGGED_F16, torch.bfloat16: RAGGED_BF16, torch.float32: RAGGED_F32}
 
 EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_strided", "ragged_attn_padded", "ragged_unpack",
-           "ragged_repack", "ragged_cls_extract", "ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", "ragged_token_scores_l2", "ragged_keep_topk", "ragged_noop", "ragged_status_string", "ragged_version")
+           "ragged_repack", "ragged_cls_extract", "ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm",
+           "ragged_token_scores_l2", "ragged_keep_topk", "ragged_noop", "ragged_status_string", "ragged_version")
 
 _lib = None
 
@@ -229,13 +230,13 @@ def ragged_pack_attn_unpack(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o,
                             fill_mode: int = 0, stream=None) -> None:
     """ragged_pack(x, keep) + ragged_attn(q, k, v) + ragged_unpack(o -> out) in one launch; q, k, v,
     o, packed, gather_idx hold cap >= B*N rows."""
-    _check("ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", "ragged_token_scores_l2", "ragged_keep_topk", load().ragged_pack_attn_unpack(
+    _check("ragged_pack_attn_unpack", load().ragged_pack_attn_unpack(
         *_step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream)))
 
 
 def prepare_pack_attn_unpack(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale: float,
                              fill_mode: int = 0, stream=None) -> "Prepared":
-    return Prepared("ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm", "ragged_token_scores_l2", "ragged_keep_topk", load().ragged_pack_attn_unpack,
+    return Prepared("ragged_pack_attn_unpack", load().ragged_pack_attn_unpack,
                     _step_args(x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out, scale, fill_mode, stream),
                     (x, keep, q, k, v, packed, cu_seqlens, gather_idx, o, out))
 

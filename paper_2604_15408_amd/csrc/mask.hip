@@ -5,8 +5,8 @@
 //     accumulation: a square of a 16-bit value is exact in fp64, so for ordinary data the score does
 //     not depend on the summation order and ranking decisions agree with any other exact evaluation.
 //   keep_topk_kernel: per image, token 0 (the class token) is kept and, of the others, the k-1 with
-//     the largest score (equal scores: lower position first).  One work-group per image, scores in
-//     LDS, an O(N^2) count per token -- N is a few hundred.
+//     the largest score (equal scores: lower position first).  Scores of the image in LDS, an O(N)
+//     count per token split over four lanes -- N is a few hundred.
 #include "common.h"
 #include "mfma_lds.h"
 
@@ -36,21 +36,29 @@ void token_scores_l2_kernel(const uint4* __restrict__ x, int64_t rows, int chunk
     if (lane == 0) scores[row] = acc;
 }
 
+// One work-group per (image, 64 tokens): four lanes share a token and split the range of rivals
+// u = 1 .. N-1 between them (u = part, part+4, ...), so the counting loop is a quarter as long and the
+// image's scores are read from LDS; the four partial counts meet in a quad reduction.
+constexpr int kTopkTokens = kBlockThreads / 4;
+
 __global__ __launch_bounds__(kBlockThreads)
-void keep_topk_kernel(const double* __restrict__ scores, int N, int k, uint8_t* __restrict__ keep) {
+void keep_topk_kernel(const double* __restrict__ scores, int N, int k, int chunks, uint8_t* __restrict__ keep) {
     __shared__ double s[kMaxMaskTokens];
-    const double* mine = scores + (int64_t)blockIdx.x * N;
-    for (int t = threadIdx.x; t < N; t += kBlockThreads) s[t] = mine[t];
+    const int img = blockIdx.x / chunks;
+    const int t = (blockIdx.x - img * chunks) * kTopkTokens + (threadIdx.x >> 2);
+    const int part = threadIdx.x & 3;
+    const double* mine = scores + (int64_t)img * N;
+    for (int u = threadIdx.x; u < N; u += kBlockThreads) s[u] = mine[u];
     __syncthreads();
-    for (int t = threadIdx.x; t < N; t += kBlockThreads) {
-        const double st = s[t];
-        int before = 0;
-        for (int u = 1; u < N; ++u) {
-            const double su = s[u];
-            before += (u != t && (su > st || (su == st && u < t))) ? 1 : 0;
-        }
-        keep[(int64_t)blockIdx.x * N + t] = (uint8_t)((t == 0 || before < k - 1) ? 1 : 0);
+    const double st = s[t < N ? t : 0];
+    int before = 0;
+    for (int u = 1 + part; u < N; u += 4) {
+        const double su = s[u];
+        before += (u != t && (su > st || (su == st && u < t))) ? 1 : 0;
     }
+    before += __shfl_xor(before, 1, kWaveSize);
+    before += __shfl_xor(before, 2, kWaveSize);
+    if (part == 0 && t < N) keep[(int64_t)img * N + t] = (uint8_t)((t == 0 || before < k - 1) ? 1 : 0);
 }
 
 }  // namespace
@@ -69,7 +77,8 @@ hipError_t launch_token_scores_l2(const void* x, int64_t rows, int C, ragged_dty
 }
 
 hipError_t launch_keep_topk(const double* scores, int B, int N, int k, uint8_t* keep, hipStream_t stream) {
-    hipLaunchKernelGGL(keep_topk_kernel, dim3(B), dim3(kBlockThreads), 0, stream, scores, N, k, keep);
+    const int chunks = (N + kTopkTokens - 1) / kTopkTokens;
+    hipLaunchKernelGGL(keep_topk_kernel, dim3(B * chunks), dim3(kBlockThreads), 0, stream, scores, N, k, chunks, keep);
     return hipGetLastError();
 }
 

@@ -121,6 +121,23 @@ def late_blocks_case(torch, w, label: str, depth: int = 8):
     return rec
 
 
+def mask_producer_case(torch, B: int = 32, N: int = 197, k: int = 40):
+    """The keep-mask producer in front of pack: fp64 l2 scores + per-image top-k, then pack."""
+    from . import binding
+    dev = "cuda:0"
+    x = wl.deit_b_pruned(1.0, B, "f16", 1008).features().to(dev)
+    C = x.shape[2]
+    scores = torch.zeros(B, N, dtype=torch.float64, device=dev)
+    keep = torch.zeros(B, N, dtype=torch.uint8, device=dev)
+    out = {}
+    for name, fn in (("token_scores_l2", lambda: binding.ragged_token_scores_l2(x, scores)),
+                     ("keep_topk", lambda: binding.ragged_keep_topk(scores, k, keep))):
+        g = capture(torch, fn, REPLICAS)
+        out[name] = event_time_us(torch, g.replay, iters=30)[0] / REPLICAS
+    return {"case": "mask_producer", "B": B, "N": N, "C": C, "k": k, "kernel_us": out,
+            "scores_gbs": B * N * C * 2 / (out["token_scores_l2"] * 1e-6) / 1e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default=None)
@@ -142,6 +159,12 @@ def main():
 
     if want("headline"):
         emit(case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "headline"))
+    if want("uniform"):
+        emit(case(torch, wl.uniform(32, 40), "uniform_lengths"))        # the paper's BS=32, 40 tok/img row
+        emit(case(torch, wl.uniform(1, 40), "uniform_lengths"))
+        emit(case(torch, wl.uniform(32, 197), "uniform_lengths"))
+    if want("mask_producer"):
+        emit(mask_producer_case(torch))
     if want("sweep"):
         pad_us = None
         for w in wl.sweep():

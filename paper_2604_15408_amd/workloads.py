@@ -117,6 +117,13 @@ def deit_b_pruned(keep_prob: float = 0.2, B: int = 32, dtype: str = "f16",
                     note=f"1+Binomial(196,{keep_prob:g})")
 
 
+def uniform(B: int, per_image: int, N: int = 197, dtype: str = "f16", seed: int = 1007) -> Workload:
+    """Every image keeps exactly `per_image` tokens (class token + a seeded random subset): the
+    uniform-length setting of the paper's kernel-latency tables (e.g. BS=32, 40 tokens per image)."""
+    return Workload(f"uniform{per_image}_bs{B}_{dtype}", B, N, 12, 64, dtype, seed,
+                    keep_exact(N, [per_image] * B, seed), note=f"exactly {per_image} per image")
+
+
 SWEEP_KEEP_PROBS = (1.0, 0.8, 0.6, 0.4, 0.2, 0.1)
 
 

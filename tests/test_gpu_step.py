@@ -135,3 +135,64 @@ def test_graph_replays_match_eager():
         for n, t in bufs.items():
             a, b = (t.view(torch.int16), want[n].view(torch.int16)) if t.dtype == torch.float16 else (t, want[n])
             assert torch.equal(a, b), n
+
+
+def test_prepared_calls_reproduce_checked_calls():
+    """Every pre-marshalled call (what the benchmark's fastest modes issue) gives the checked call's result."""
+    from paper_2604_15408_amd.harness import PaddedPath, Path
+    w = wl.deit_b_pruned(0.3, B=6)
+    p = Path(w, fill_mode=1)
+    p.step()
+    torch.cuda.synchronize()
+    want = {n: getattr(p, n).clone() for n in ("packed", "cu", "gidx", "o", "out")}
+
+    def same():
+        T = w.T
+        assert torch.equal(p.cu, want["cu"]) and torch.equal(p.gidx[:T], want["gidx"][:T])
+        for n in ("packed", "o"):
+            assert torch.equal(getattr(p, n)[:T].view(torch.int16), want[n][:T].view(torch.int16)), n
+        assert torch.equal(p.out.view(torch.int16), want["out"].view(torch.int16))
+
+    for make in (p.prepared_step, p.prepared_one_launch):
+        for n in ("packed", "o", "out"):
+            getattr(p, n).zero_()
+        p.cu.zero_()
+        call = make()
+        call()
+        torch.cuda.synchronize()
+        same()
+    pad = PaddedPath(w, 1)
+    pad.run()
+    torch.cuda.synchronize()
+    ref = pad.o.clone()
+    pad.o.zero_()
+    pad.prepared()()
+    torch.cuda.synchronize()
+    assert torch.equal(pad.o.view(torch.int16), ref.view(torch.int16))
+    # the remaining prepare_* helpers
+    x = torch.randn(40, 128, device=DEV).half()
+    wgt = torch.randn(128, 128, device=DEV).half()
+    y1, y2 = torch.zeros(40, 128, device=DEV).half(), torch.zeros(40, 128, device=DEV).half()
+    binding.ragged_linear(x, wgt, None, None, y1)
+    binding.prepare_linear(x, wgt, None, None, y2)()
+    g, bta = torch.ones(128, device=DEV).half(), torch.zeros(128, device=DEV).half()
+    n1, n2 = torch.zeros_like(x), torch.zeros_like(x)
+    binding.ragged_layernorm(x, g, bta, n1)
+    binding.prepare_layernorm(x, g, bta, n2)()
+    cu = torch.tensor([0, 10, 40], dtype=torch.int32, device=DEV)
+    c1, c2 = torch.zeros(2, 128, device=DEV).half(), torch.zeros(2, 128, device=DEV).half()
+    binding.ragged_cls_extract(x, cu, c1)
+    binding.prepare_cls_extract(x, cu, c2)()
+    keep_rows = (torch.arange(40, device=DEV) % 3 != 0).to(torch.uint8)
+    outs = []
+    for fn in (binding.ragged_repack, lambda *a: binding.prepare_repack(*a)()):
+        po, co, go = torch.zeros_like(x), torch.zeros_like(cu), torch.zeros(40, dtype=torch.int32, device=DEV)
+        fn(x, keep_rows, cu, po, co, go)
+        outs.append((po, co, go))
+    qkv = torch.randn(40, 3, 2, 64, device=DEV).half()
+    o1, o2 = torch.zeros(40, 2, 64, device=DEV).half(), torch.zeros(40, 2, 64, device=DEV).half()
+    binding.ragged_attn_strided(qkv[:, 0], qkv[:, 1], qkv[:, 2], o1, cu, 30, 0.125)
+    binding.prepare_attn_strided(qkv[:, 0], qkv[:, 1], qkv[:, 2], o2, cu, 30, 0.125)()
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2) and torch.equal(n1, n2) and torch.equal(c1, c2) and torch.equal(o1, o2)
+    assert all(torch.equal(a, b) for a, b in zip(*outs))
