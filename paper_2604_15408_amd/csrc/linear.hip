@@ -32,6 +32,7 @@ namespace {
 
 constexpr int kTK = 64;                          // contraction elements per stage: 128-byte LDS rows
 constexpr int kBigTileMinGroups = 400;           // use 256 x 256 tiles from this many of them on
+constexpr int kSplitMaxGroups = 128;             // split the k-loop inside the group up to this many 128 x 128 tiles
 
 // GELU(t) = t * Phi(t) with Phi from erfc(z) ~ poly(u) * exp(-z^2), u = 1 / (1 + p z), z = |t| / sqrt 2.
 __device__ __forceinline__ float gelu_erf(float t) {
@@ -81,8 +82,14 @@ __device__ __forceinline__ void pack16(BF16, const float (&v)[16], uint4& a, uin
 // size (a 128 x 128 tile needs 1/64 byte per flop, which at MFMA rate is more than the L2s deliver;
 // 256 x 256 halves it), so large problems use 4 x 2 wavefronts of 64 x 128 and small ones, where
 // filling the 256 CUs matters more, 2 x 2 wavefronts of 64 x 64.
-template <typename In, int ACT, bool HAS_RES, int WNW, int WMW, int MT, int STAGES>
-__global__ __launch_bounds__(kWaveSize * WNW * WMW, (WNW * WMW == 4 && STAGES == 2) ? 2 : 1)
+//
+// KSPLIT = 2 (small grids only): the work-group has two sets of WNW x WMW wavefronts; set g runs the same
+// loop over the g-th half of the k-steps with a stage ring of its own, so the serial chain of k-steps --
+// what a grid of at most one work-group per CU waits for -- is half as long and each SIMD has two
+// wavefronts to interleave.  At the end set 1 hands its accumulators to set 0 through LDS (fixed
+// order: the result does not depend on timing) and set 0 runs the epilogue.
+template <typename In, int ACT, bool HAS_RES, int WNW, int WMW, int MT, int STAGES, int KSPLIT>
+__global__ __launch_bounds__(kWaveSize * WNW * WMW * KSPLIT, (WNW * WMW * KSPLIT == 4 && STAGES == 2) ? 2 : 1)
 void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
                    const uint16_t* __restrict__ bias, const uint16_t* __restrict__ res,
                    uint16_t* __restrict__ y, int rows_cap, const int32_t* __restrict__ rows_dev, int N, int K,
@@ -92,7 +99,8 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     constexpr int TN = 64 * WNW, TM = 16 * MT * WMW;
     constexpr int kXBytes = TM * kTK * 2, kWBytes = TN * kTK * 2;       // operand tiles of one stage
     constexpr int kStageBytes = kXBytes + kWBytes;
-    __shared__ __attribute__((aligned(1024))) uint4 stage_lds[STAGES * kStageBytes / 16];   // [stage][x | w]
+    __shared__ __attribute__((aligned(1024))) uint4 stage_lds[KSPLIT * STAGES * kStageBytes / 16];   // [set][stage][x | w]
+    static_assert(KSPLIT == 1 || STAGES * kStageBytes >= 4 * MT * 16 * kWaveSize * WAVES, "the hand-over needs room in a ring");
 
     const int xcd = blockIdx.x % kXcds;
     const int local = blockIdx.x / kXcds;
@@ -106,7 +114,9 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_wg = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kset = wave_wg / WAVES;                          // which half of the k-steps (0 if KSPLIT == 1)
+    const int wave = wave_wg - kset * WAVES;                   // wavefront inside its set
     const int col = lane & 15;
     const int g = lane >> 4;
     const int wn = wave % WNW, wm = wave / WNW;                // this wavefront's feature / token block
@@ -116,7 +126,8 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     // chunk (lane%8) ^ ((row>>1)&3).
     constexpr int kXI = TM / 8 / WAVES, kWI = TN / 8 / WAVES;  // load instructions per wavefront per stage
     static_assert(TM % (8 * WAVES) == 0 && TN % (8 * WAVES) == 0, "tile rows must split over the wavefronts");
-    const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)stage_lds);
+    const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)stage_lds) +
+                          kset * STAGES * kStageBytes;         // this set's ring
     const uint32_t row_bytes = (uint32_t)K * 2u;
     const uint32_t chunk = 16u * ((lane & 7) ^ ((lane >> 4) & 3));
     uint32_t voff_x[kXI], voff_w[kWI];
@@ -128,8 +139,9 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     }
 #pragma unroll
     for (int i = 0; i < kWI; ++i) voff_w[i] = (uint32_t)(8 * (kWI * wave + i) + (lane >> 3)) * row_bytes + chunk;
-    const uint16_t* x_base = x + (int64_t)m0 * K;              // wave-uniform; advances by kTK per step
-    const uint16_t* w_base = w + (int64_t)n0 * K;
+    const int ksteps = K / kTK / KSPLIT;                       // k-steps of this set (the host makes it divide)
+    const uint16_t* x_base = x + (int64_t)m0 * K + kset * ksteps * kTK;   // wave-uniform; advances by kTK per step
+    const uint16_t* w_base = w + (int64_t)n0 * K + kset * ksteps * kTK;
     auto issue = [&](int kt, int s) {
         const uint32_t dst = lds0 + s * kStageBytes;
 #pragma unroll
@@ -174,7 +186,6 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
             for (int mt = 0; mt < MT; ++mt)
                 acc[j][mt] = In::mfma(as_vec8<vec8>(a[j]), as_vec8<vec8>(b[mt]), acc[j][mt]);
     };
-    const int ksteps = K / kTK;
     constexpr int kPer = kXI + kWI;         // load instructions of this wavefront per stage
     // wait until at most `later` stages younger than the wanted one are still in flight
     auto wait_stage = [&](int later) {
@@ -191,23 +202,55 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     uint4 a0[4], b0[MT], a1[4], b1[MT];
     read_frags(lds0, 0, a0, b0);
     int buf = 0;                                               // buffer of step kt
-    for (int kt = 0; kt < ksteps; ++kt) {
+    // Steady state (a next step exists) is kept free of conditional LDS traffic, so that the wait
+    // in front of the second half's MFMAs covers exactly the fragments they read and not the ones
+    // just requested for the next step; the last step is peeled.
+    for (int kt = 0; kt + 1 < ksteps; ++kt) {
         const int buf_next = buf + 1 == STAGES ? 0 : buf + 1;
+        // the first half's fragments were requested a half-step ago: retire them now, so that the wait in
+        // front of their MFMAs does not also cover the requests that follow (the LDS counter holds 15)
+        __builtin_amdgcn_s_waitcnt(0xC07F);                    // lgkmcnt(0)
         read_frags(lds0 + buf * kStageBytes, 1, a1, b1);
         __builtin_amdgcn_sched_barrier(0);
         mma(a0, b0);
         __builtin_amdgcn_sched_barrier(0);
-        if (kt + 1 < ksteps) {
-            const int last_issued = kt + STAGES - 1 < ksteps - 1 ? kt + STAGES - 1 : ksteps - 1;
-            wait_stage(last_issued - (kt + 1));                // step kt+1 has landed
-            __syncthreads();                // ... for every wavefront, and all of them hold step kt in registers
-            if (kt + STAGES < ksteps) issue(kt + STAGES, buf);
-            read_frags(lds0 + buf_next * kStageBytes, 0, a0, b0);
-        }
+        const int last_issued = kt + STAGES - 1 < ksteps - 1 ? kt + STAGES - 1 : ksteps - 1;
+        wait_stage(last_issued - (kt + 1));                    // step kt+1 has landed
+        __syncthreads();                    // ... for every wavefront, and all of them hold step kt in registers
+        if (kt + STAGES < ksteps) issue(kt + STAGES, buf);
+        read_frags(lds0 + buf_next * kStageBytes, 0, a0, b0);
         __builtin_amdgcn_sched_barrier(0);
         mma(a1, b1);
         __builtin_amdgcn_sched_barrier(0);
         buf = buf_next;
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    read_frags(lds0 + buf * kStageBytes, 1, a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(a0, b0);
+    mma(a1, b1);
+
+    if (KSPLIT == 2) {
+        // set 1 -> LDS -> set 0, one 16-byte slot per (tile, thread): conflict-free and in a fixed order
+        const uint32_t slot0 = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)stage_lds) +
+                               16u * (wave * kWaveSize + lane);
+        __syncthreads();                                       // every ring is out of use
+        if (kset == 1) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    *reinterpret_cast<__attribute__((address_space(3))) f32x4*>(
+                        static_cast<uintptr_t>(slot0 + (j * MT + mt) * 16 * kWaveSize * WAVES)) = acc[j][mt];
+        }
+        __syncthreads();
+        if (kset == 1) return;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[j][mt] += *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
+                    static_cast<uintptr_t>(slot0 + (j * MT + mt) * 16 * kWaveSize * WAVES));
     }
 
     // ---- epilogue: this lane owns, for token m0 + wm*16*MT + 16*mt + col, features n_base + 4j + r
@@ -330,42 +373,48 @@ void layernorm_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict
     }
 }
 
-template <typename In, int WNW, int WMW, int MT, int STAGES>
+template <typename In, int WNW, int WMW, int MT, int STAGES, int KSPLIT>
 hipError_t launch_linear_shape(const void* x, const void* w, const void* bias, const void* res, void* y,
                                int rows_cap, const int32_t* rows_dev, int N, int K, int act, hipStream_t stream) {
     constexpr int TN = 64 * WNW, TM = 16 * MT * WMW;
     const int n_tiles = N / TN;
     const int m_tiles = (rows_cap + TM - 1) / TM;
     const int m_tiles8 = (m_tiles + kXcds - 1) / kXcds * kXcds;
-    const dim3 grid(m_tiles8 * n_tiles), block(kWaveSize * WNW * WMW);
+    const dim3 grid(m_tiles8 * n_tiles), block(kWaveSize * WNW * WMW * KSPLIT);
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     const uint16_t* wp = static_cast<const uint16_t*>(w);
     const uint16_t* bp = static_cast<const uint16_t*>(bias);
     const uint16_t* rp = static_cast<const uint16_t*>(res);
     uint16_t* yp = static_cast<uint16_t*>(y);
     if (act == 1 && res)
-        hipLaunchKernelGGL((linear_kernel<In, 1, true, WNW, WMW, MT, STAGES>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        hipLaunchKernelGGL((linear_kernel<In, 1, true, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else if (act == 1)
-        hipLaunchKernelGGL((linear_kernel<In, 1, false, WNW, WMW, MT, STAGES>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        hipLaunchKernelGGL((linear_kernel<In, 1, false, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else if (res)
-        hipLaunchKernelGGL((linear_kernel<In, 0, true, WNW, WMW, MT, STAGES>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        hipLaunchKernelGGL((linear_kernel<In, 0, true, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else
-        hipLaunchKernelGGL((linear_kernel<In, 0, false, WNW, WMW, MT, STAGES>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        hipLaunchKernelGGL((linear_kernel<In, 0, false, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     return hipGetLastError();
 }
 
 // Shape choice from what the host knows (row capacity and N):
 //   * 256 x 256 tiles, two stages, when there are enough of them for well over one round of the
 //     256 CUs (the large tile halves the L2 -> LDS bytes per flop);
-//   * else 128 x 128 tiles with two stages, two work-groups per CU.  (A four-stage ring for grids of
-//     at most one work-group per CU was measured and is slower: 28 against 16 us at 1334 x 2304 x 768.)
+//   * else 128 x 128 tiles with two stages, two work-groups per CU; when the capacity gives at most 128
+//     such tiles (half the CUs idle, the k-loop is a serial chain), the k-loop is split inside the
+//     group: 27.8 against 33.3 us at 1334 x 768 x 3072, but slower once the grid fills the chip
+//     (19.9 against 16.0 us at 1334 x 2304 x 768), hence the limit.  (A four-stage ring for small
+//     grids was measured too and is slower: 28 against 16 us at 1334 x 2304 x 768.)
 template <typename In>
 hipError_t launch_linear_typed(const void* x, const void* w, const void* bias, const void* res, void* y,
                                int rows_cap, const int32_t* rows_dev, int N, int K, int act, hipStream_t stream) {
     const int64_t big_tiles = (int64_t)((rows_cap + 255) / 256) * (N / 256);
     if (N % 256 == 0 && big_tiles >= kBigTileMinGroups)
-        return launch_linear_shape<In, 4, 2, 8, 2>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
-    return launch_linear_shape<In, 2, 2, 4, 2>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
+        return launch_linear_shape<In, 4, 2, 8, 2, 1>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
+    const int64_t small_tiles = (int64_t)((rows_cap + 127) / 128) * (N / 128);
+    if (small_tiles <= kSplitMaxGroups && (K / kTK) % 2 == 0 && K / kTK >= 4)
+        return launch_linear_shape<In, 2, 2, 4, 2, 2>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
+    return launch_linear_shape<In, 2, 2, 4, 2, 1>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
 }
 
 }  // namespace

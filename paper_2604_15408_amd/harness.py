@@ -279,14 +279,19 @@ class PackedBlocks:
     launch takes the packed row count from cu_seqlens[B] on the device, so the loop is capturable
     and its cost follows the number of kept tokens."""
 
-    def __init__(self, w, depth: int = 8, shared_weights: bool = True):
+    def __init__(self, w, depth: int = 8, shared_weights: bool = True, rows_cap: int | None = None):
+        """rows_cap: row capacity of the packed buffers.  B*N always works; a pruning method that keeps a
+        fixed number of tokens per image knows T on the host and can pass it, which lets the linear
+        layers size their grids and pick their tiles for the real row count."""
         import torch
         from paper_2604_15408_amd import binding
         from paper_2604_15408_amd import workloads as wl
         self.torch, self.b, self.w, self.depth = torch, binding, w, depth
         dev = "cuda:0"
         B, N, C, H, D = w.B, w.N, w.C, w.H, w.D
-        cap = B * N
+        cap = B * N if rows_cap is None else int(rows_cap)
+        if cap < w.T:
+            raise ValueError("rows_cap is smaller than the number of kept tokens")
         self.cap, self.hidden = cap, 4 * C
         tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
         self.x_in = w.features().to(dev)

@@ -98,11 +98,11 @@ def stay_packed_case(torch):
             "tokens_per_s": pipe.tokens / (wall_graph * 1e-6)}
 
 
-def late_blocks_case(torch, w, label: str, depth: int = 8):
+def late_blocks_case(torch, w, label: str, depth: int = 8, tight_cap: bool = False):
     """pack + `depth` encoder blocks on the packed rows + CLS read, in one HIP graph, next to the same
     blocks over all B*N rows (what a padded pipeline computes)."""
     def timed(workload):
-        pb = PackedBlocks(workload, depth)
+        pb = PackedBlocks(workload, depth, rows_cap=workload.T if tight_cap else None)
         pb.run()
         torch.cuda.synchronize()
         g = capture(torch, pb.run)
@@ -111,6 +111,7 @@ def late_blocks_case(torch, w, label: str, depth: int = 8):
     pb, gpu_us, wall_us = timed(w)
     full = wl.deit_b_pruned(1.0, w.B, w.dtype, w.seed) if w.N == 197 else None
     rec = {"case": label, "workload": w.name, "B": w.B, "N": w.N, "T": w.T, "depth": depth,
+           "rows_cap": w.T if tight_cap else w.B * w.N,
            "kernels_in_graph": pb.launches, "graph_gpu_us": gpu_us, "graph_wall_us": wall_us,
            "us_per_block": gpu_us / depth, "tflops": pb.flops() / gpu_us / 1e6,
            "tokens_per_s": w.T * depth / (wall_us * 1e-6), "images_per_s_through_late_blocks": w.B / (wall_us * 1e-6)}
@@ -182,6 +183,8 @@ def main():
         emit(stay_packed_case(torch))
     if want("late_blocks"):
         emit(late_blocks_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "late_blocks_headline"))
+        # a fixed number of kept tokens per image: T is known on the host and is the row capacity
+        emit(late_blocks_case(torch, wl.uniform(32, 40), "late_blocks_uniform40_tight_cap", tight_cap=True))
         emit(late_blocks_case(torch, wl.deit_b_pruned(0.5, 8, "f16", 1005), "late_blocks_bs8_keep0.5"))
         emit(late_blocks_case(torch, wl.deit_b_pruned(1.0, 64, "f16", 1006), "late_blocks_bs64_dense"))
     if args.out:
