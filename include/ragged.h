@@ -219,14 +219,17 @@ int ragged_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int
  *   rows_dev                NULL, or a DEVICE pointer to the number of valid rows (for example
  *                           &cu_seqlens[B]); rows processed = min(rows_cap, *rows_dev), read on the
  *                           device, so the call stays capturable.  Rows beyond are left untouched.
+ *   rows_hint               0, or the caller's estimate of the valid row count (1 <= rows_hint <=
+ *                           rows_cap), e.g. keep ratio * B * N: it only chooses the launch shape (the
+ *                           result and the rows written do not depend on it).  0 means rows_cap.
  *   act                     0: none, 1: GELU in its erf form t * Phi(t)
  *
  * Supported: dt = F16 or BF16, N a multiple of 128, K a multiple of 64 and <= 2^22.  MFMA with fp32
  * accumulation; bias, activation and residual are applied in fp32 before the single rounding to dt.
  */
 int ragged_linear(const void* x, const void* w, const void* bias, const void* residual, void* y,
-                  int64_t rows_cap, const int32_t* rows_dev, int N, int K, int act, ragged_dtype dt,
-                  void* stream);
+                  int64_t rows_cap, const int32_t* rows_dev, int64_t rows_hint, int N, int K, int act,
+                  ragged_dtype dt, void* stream);
 
 /*
  * ragged_layernorm -- LayerNorm over the feature dimension of packed rows (same blocks as above):

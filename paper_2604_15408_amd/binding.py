@@ -55,7 +55,7 @@ def load() -> ctypes.CDLL:
         lib.ragged_pack_attn_unpack.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, i64, vp, vp,
                                                 vp, vp, i32, vp]
         lib.ragged_pack_attn_unpack.restype = i32
-        lib.ragged_linear.argtypes = [vp, vp, vp, vp, vp, i64, vp, i32, i32, i32, i32, vp]
+        lib.ragged_linear.argtypes = [vp, vp, vp, vp, vp, i64, vp, i64, i32, i32, i32, i32, vp]
         lib.ragged_linear.restype = i32
         lib.ragged_layernorm.argtypes = [vp, vp, vp, vp, i64, vp, i32, f32, i32, vp]
         lib.ragged_layernorm.restype = i32
@@ -251,23 +251,27 @@ def _rows_dev(rows_dev):
     return rows_dev.data_ptr()
 
 
-def _linear_args(x, w, bias, residual, y, rows_dev, act, stream):
+def _linear_args(x, w, bias, residual, y, rows_dev, act, stream, rows_hint=0):
     rows, K = x.shape
     N = w.shape[0]
     return (_dev(x, "x", (torch.float16, torch.bfloat16)), _dev(w, "w", x.dtype, (N, K)),
             None if bias is None else _dev(bias, "bias", x.dtype, (N,)),
             None if residual is None else _dev(residual, "residual", x.dtype, (rows, N)),
-            _dev(y, "y", x.dtype, (rows, N)), rows, _rows_dev(rows_dev), N, K, {"none": 0, "gelu": 1}[act],
+            _dev(y, "y", x.dtype, (rows, N)), rows, _rows_dev(rows_dev), int(rows_hint), N, K, {"none": 0, "gelu": 1}[act],
             _DTYPE_CODE[x.dtype], _stream(stream))
 
 
-def ragged_linear(x, w, bias, residual, y, rows_dev=None, act: str = "none", stream=None) -> None:
-    """y = act(x @ w.T + bias) + residual over the first min(rows, *rows_dev) rows.  x [rows,K], w [N,K]."""
-    _check("ragged_linear", load().ragged_linear(*_linear_args(x, w, bias, residual, y, rows_dev, act, stream)))
+def ragged_linear(x, w, bias, residual, y, rows_dev=None, act: str = "none", stream=None, rows_hint: int = 0) -> None:
+    """y = act(x @ w.T + bias) + residual over the first min(rows, *rows_dev) rows.  x [rows,K], w [N,K].
+    rows_hint: an estimate of *rows_dev known on the host (0 = rows); it only picks the launch shape."""
+    _check("ragged_linear",
+           load().ragged_linear(*_linear_args(x, w, bias, residual, y, rows_dev, act, stream, rows_hint)))
 
 
-def prepare_linear(x, w, bias, residual, y, rows_dev=None, act: str = "none", stream=None) -> "Prepared":
-    return Prepared("ragged_linear", load().ragged_linear, _linear_args(x, w, bias, residual, y, rows_dev, act, stream),
+def prepare_linear(x, w, bias, residual, y, rows_dev=None, act: str = "none", stream=None,
+                   rows_hint: int = 0) -> "Prepared":
+    return Prepared("ragged_linear", load().ragged_linear,
+                    _linear_args(x, w, bias, residual, y, rows_dev, act, stream, rows_hint),
                     (x, w, bias, residual, y, rows_dev))
 
 

@@ -25,6 +25,11 @@ HIPCC_FLAGS = [
 ]
 
 
+# linear.hip: keep MFMA results in plain VGPRs.  Where LDS use limits a CU to one work-group the
+# compiler otherwise moves accumulators to AGPRs and copies them back and forth around every MFMA.
+PER_FILE_FLAGS = {"linear.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if cand and (os.path.sep not in cand or os.path.exists(cand)):
@@ -39,7 +44,7 @@ def build(verbose: bool = False, extra_flags=()) -> Path:
 
     def compile_one(name: str) -> Path:
         obj = BUILD_DIR / (name + ".o")
-        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-c", str(CSRC / name), "-o", str(obj)]
+        cmd = [hipcc, *HIPCC_FLAGS, *PER_FILE_FLAGS.get(name, []), *extra_flags, "-c", str(CSRC / name), "-o", str(obj)]
         res = subprocess.run(cmd, capture_output=True, text=True)
         noise = "is not a recognized feature for this target"
         err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)

@@ -40,7 +40,8 @@ hipError_t launch_step(const void* x, const uint8_t* keep, const void* q, const 
                        hipStream_t stream);
 // y = act(x w^T + bias) (+ residual) over packed rows; rows = min(rows_cap, *rows_dev) if rows_dev != null
 hipError_t launch_linear(const void* x, const void* w, const void* bias, const void* res, void* y, int rows_cap,
-                         const int32_t* rows_dev, int N, int K, int act, ragged_dtype dt, hipStream_t stream);
+                         const int32_t* rows_dev, int rows_hint, int N, int K, int act, ragged_dtype dt,
+                         hipStream_t stream);
 hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int rows_cap,
                             const int32_t* rows_dev, int C, float eps, ragged_dtype dt, hipStream_t stream);
 int layernorm_max_width();

@@ -5,16 +5,16 @@
 // linear_kernel:  y[m][n] = act( sum_k x[m][k] * w[n][k] + bias[n] ) (+ residual[m][n])
 //   x [rows, K] activations, w [N, K] weights (one output feature per row, so both operands are
 //   contiguous along k, which is how an MFMA lane wants them: 8 consecutive k per 16-byte read).
-//   One work-group computes a tile of tokens x features (128 x 128 with four wavefronts or 256 x 256
-//   with eight); a wavefront owns 64 features x 64 or 128 tokens as 4 x 4 or 4 x 8 MFMA 16x16x32
-//   tiles with fp32 accumulators.  The product is formed
+//   One work-group computes a tile of tokens x features (256 x 256 with eight wavefronts, 128 x 128
+//   with four, or 64 x 64 with one wavefront per half of the k-loop); a wavefront owns 64 features
+//   x 64 or 128 tokens as 4 x 4 or 4 x 8 MFMA 16x16x32 tiles with fp32 accumulators.  The product is formed
 //   TRANSPOSED (features x tokens: W is the A operand, x the B operand), so that a lane ends up
 //   with, for one token, 16 consecutive output features -- two 16-byte stores per token -- once the
 //   A-operand rows are relabelled: MFMA row m' of feature tile j stands for feature
 //   16*(m'/4) + 4*j + m'%4 of the quadrant.
 //   Operand tiles (rows x 64 k = 128-byte rows) are brought into LDS by direct global->LDS
 //   loads, row-major with the chunk swizzle c ^ ((row>>1)&3) that makes every 16-byte operand read
-//   conflict-free, in a ring of 2 or 4 stages; a stage is refilled as soon as every wavefront holds
+//   conflict-free, in a ring of two stages; a stage is refilled as soon as every wavefront holds
 //   it in registers.
 //   Epilogue in registers: bias, optional GELU (erf form, Abramowitz-Stegun 7.1.26, |error| 1.5e-7,
 //   written so the negative tail does not cancel), optional residual, conversion, store.
@@ -24,6 +24,7 @@
 //
 // Rows: the caller passes a capacity and, optionally, a device pointer to the real row count (for
 // example &cu_seqlens[B]); work-groups past it exit, so nothing is read back to the host.
+#include <type_traits>
 #include "common.h"
 #include "mfma_lds.h"
 
@@ -32,7 +33,7 @@ namespace {
 
 constexpr int kTK = 64;                          // contraction elements per stage: 128-byte LDS rows
 constexpr int kBigTileMinGroups = 400;           // use 256 x 256 tiles from this many of them on
-constexpr int kSplitMaxGroups = 128;             // split the k-loop inside the group up to this many 128 x 128 tiles
+constexpr int kSplitMaxGroups = 128;             // 64 x 64 tiles with the k-loop split in the group up to this many 128 x 128 tiles
 
 // GELU(t) = t * Phi(t) with Phi from erfc(z) ~ poly(u) * exp(-z^2), u = 1 / (1 + p z), z = |t| / sqrt 2.
 __device__ __forceinline__ float gelu_erf(float t) {
@@ -80,16 +81,21 @@ __device__ __forceinline__ void pack16(BF16, const float (&v)[16], uint4& a, uin
 // Shape of a work-group: WNW x WMW wavefronts, each owning 64 features x 16*MT tokens, i.e. a tile of
 // TN = 64*WNW features x TM = 16*MT*WMW tokens.  The L2 -> LDS traffic per flop falls with the tile
 // size (a 128 x 128 tile needs 1/64 byte per flop, which at MFMA rate is more than the L2s deliver;
-// 256 x 256 halves it), so large problems use 4 x 2 wavefronts of 64 x 128 and small ones, where
-// filling the 256 CUs matters more, 2 x 2 wavefronts of 64 x 64.
+// 256 x 256 halves it), so large problems use 4 x 2 wavefronts of 64 x 128, mid-sized ones 2 x 2
+// wavefronts of 64 x 64 and small ones, where filling the 256 CUs matters most, single wavefronts.
 //
-// KSPLIT = 2 (small grids only): the work-group has two sets of WNW x WMW wavefronts; set g runs the same
-// loop over the g-th half of the k-steps with a stage ring of its own, so the serial chain of k-steps --
-// what a grid of at most one work-group per CU waits for -- is half as long and each SIMD has two
-// wavefronts to interleave.  At the end set 1 hands its accumulators to set 0 through LDS (fixed
+// KSPLIT > 1 (small grids only): the work-group has KSPLIT sets of WNW x WMW wavefronts; set g runs the
+// same loop over the g-th part of the k-steps with a stage ring of its own, so the serial chain of
+// k-steps -- what a grid of at most one work-group per CU waits for -- is shorter and more loads are in
+// flight per CU.  At the end the other sets hand their accumulators to set 0 through LDS (summed in set
 // order: the result does not depend on timing) and set 0 runs the epilogue.
+//
+// The second launch bound asks for two wavefronts per SIMD, i.e. at most 256 registers; together with the
+// compiler option that keeps MFMA results in plain VGPRs (see the build script) it stops the compiler
+// from parking accumulators in AGPRs and copying them around every MFMA, which it does as soon as
+// the LDS use of a shape limits a CU to one work-group.
 template <typename In, int ACT, bool HAS_RES, int WNW, int WMW, int MT, int STAGES, int KSPLIT>
-__global__ __launch_bounds__(kWaveSize * WNW * WMW * KSPLIT, (WNW * WMW * KSPLIT == 4 && STAGES == 2) ? 2 : 1)
+__global__ __launch_bounds__(kWaveSize * WNW * WMW * KSPLIT, (WNW * WMW * KSPLIT >= 8) ? 1 : 8 / (WNW * WMW * KSPLIT))
 void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
                    const uint16_t* __restrict__ bias, const uint16_t* __restrict__ res,
                    uint16_t* __restrict__ y, int rows_cap, const int32_t* __restrict__ rows_dev, int N, int K,
@@ -169,10 +175,13 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
         for (int mt = 0; mt < MT; ++mt) acc[j][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- main loop, software-pipelined in half-steps of 32 k.  F0 / F1 hold the operand fragments
-    // of the two halves of a stage; the fragments of the NEXT half are requested from LDS before the
-    // 4*MT MFMAs of the current half are issued, so LDS latency hides behind the matrix core.  The
-    // barrier sits between the two halves: by then a wavefront holds all of stage t in registers,
-    // so the stage's buffer can be refilled (loads for step t+2) a whole step before it is needed.
+    // of the two halves of a stage; the fragments of the NEXT half are requested from LDS while the
+    // 4*MT MFMAs of the current half are issued, one request (and, in the second half, one global->LDS
+    // load of the stage being refilled) in front of every second MFMA: a burst of LDS requests or of
+    // load instructions would leave the matrix core idle for as long as it takes to issue, and with one
+    // wavefront per SIMD nothing else fills that gap.  The barrier sits between the two halves: by then
+    // a wavefront holds all of stage t in registers, so the stage's buffer can be refilled (loads for
+    // step t + STAGES) a whole step before it is needed.
     auto read_frags = [&](uint32_t base, int ks, uint4 (&a)[4], uint4 (&b)[MT]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) a[j] = lds_read16(base + (w_rel[j & 1] ^ (16u * ks)) + (j >> 1) * 1024);
@@ -187,6 +196,35 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
                 acc[j][mt] = In::mfma(as_vec8<vec8>(a[j]), as_vec8<vec8>(b[mt]), acc[j][mt]);
     };
     constexpr int kPer = kXI + kWI;         // load instructions of this wavefront per stage
+    constexpr int kGroups = 2 * MT;         // MFMA pairs per half-step
+    constexpr int kDmaPerGroup = (kPer + kGroups - 1) / kGroups;
+    static_assert(4 + MT <= kGroups, "one LDS request per MFMA pair must cover a half-step's fragments");
+    auto issue_one = [&](int d, int kk, uint32_t dst) {
+        if (d < kXI) dma16(dst + (kXI * wave + d) * 1024, voff_x[d], x_base + kk * kTK);
+        else dma16(dst + kXBytes + (kWI * wave + (d - kXI)) * 1024, voff_w[d - kXI], w_base + kk * kTK);
+    };
+    // one half-step: MFMAs on (ca, cb); fragments of (rbase, rks) requested into (na, nb); if DMA, the
+    // load instructions of k-step kk into the stage at dst
+    auto half_step = [&](auto dma_tag, int kk, uint32_t dst, uint32_t rbase, int rks, uint4 (&na)[4], uint4 (&nb)[MT],
+                         const uint4 (&ca)[4], const uint4 (&cb)[MT]) {
+        constexpr bool DMA = decltype(dma_tag)::value;
+#pragma unroll
+        for (int gI = 0; gI < kGroups; ++gI) {
+            if (DMA) {
+#pragma unroll
+                for (int d = gI * kDmaPerGroup; d < (gI + 1) * kDmaPerGroup && d < kPer; ++d) issue_one(d, kk, dst);
+            }
+            if (gI < 4) na[gI] = lds_read16(rbase + (w_rel[gI & 1] ^ (16u * rks)) + (gI >> 1) * 1024);
+            else if (gI < 4 + MT) nb[gI - 4] = lds_read16(rbase + (x_rel ^ (16u * rks)) + (gI - 4) * 2048);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int m = 2 * gI; m < 2 * gI + 2; ++m) {
+                const int j = m / MT, mt = m % MT;
+                acc[j][mt] = In::mfma(as_vec8<vec8>(ca[j]), as_vec8<vec8>(cb[mt]), acc[j][mt]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     // wait until at most `later` stages younger than the wanted one are still in flight
     auto wait_stage = [&](int later) {
         if (later <= 0) wait_vm<0>();
@@ -202,55 +240,54 @@ void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     uint4 a0[4], b0[MT], a1[4], b1[MT];
     read_frags(lds0, 0, a0, b0);
     int buf = 0;                                               // buffer of step kt
-    // Steady state (a next step exists) is kept free of conditional LDS traffic, so that the wait
-    // in front of the second half's MFMAs covers exactly the fragments they read and not the ones
-    // just requested for the next step; the last step is peeled.
-    for (int kt = 0; kt + 1 < ksteps; ++kt) {
+    // Steady state (a next step exists, and first the part in which a later step is still to be loaded)
+    // is free of conditional LDS traffic, so that the waits in front of the MFMAs cover exactly the
+    // fragments they read and not the ones just requested; the last step is peeled.
+    auto step = [&](auto dma_tag, int kt) {
         const int buf_next = buf + 1 == STAGES ? 0 : buf + 1;
         // the first half's fragments were requested a half-step ago: retire them now, so that the wait in
         // front of their MFMAs does not also cover the requests that follow (the LDS counter holds 15)
         __builtin_amdgcn_s_waitcnt(0xC07F);                    // lgkmcnt(0)
-        read_frags(lds0 + buf * kStageBytes, 1, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
+        half_step(std::false_type{}, 0, 0u, lds0 + buf * kStageBytes, 1, a1, b1, a0, b0);
         const int last_issued = kt + STAGES - 1 < ksteps - 1 ? kt + STAGES - 1 : ksteps - 1;
         wait_stage(last_issued - (kt + 1));                    // step kt+1 has landed
         __syncthreads();                    // ... for every wavefront, and all of them hold step kt in registers
-        if (kt + STAGES < ksteps) issue(kt + STAGES, buf);
-        read_frags(lds0 + buf_next * kStageBytes, 0, a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
+        half_step(dma_tag, kt + STAGES, lds0 + buf * kStageBytes, lds0 + buf_next * kStageBytes, 0, a0, b0, a1, b1);
         buf = buf_next;
-    }
+    };
+    int kt = 0;
+    for (; kt + STAGES < ksteps; ++kt) step(std::true_type{}, kt);
+    for (; kt + 1 < ksteps; ++kt) step(std::false_type{}, kt);
     __builtin_amdgcn_s_waitcnt(0xC07F);
     read_frags(lds0 + buf * kStageBytes, 1, a1, b1);
     __builtin_amdgcn_sched_barrier(0);
     mma(a0, b0);
     mma(a1, b1);
 
-    if (KSPLIT == 2) {
-        // set 1 -> LDS -> set 0, one 16-byte slot per (tile, thread): conflict-free and in a fixed order
-        const uint32_t slot0 = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)stage_lds) +
-                               16u * (wave * kWaveSize + lane);
+    if (KSPLIT > 1) {
+        // sets 1.. -> LDS -> set 0, one 16-byte slot per (tile, thread) inside the sender's own ring:
+        // conflict-free, and summed in set order, so the result does not depend on timing
+        const uint32_t lds_all = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)stage_lds);
+        const uint32_t slot = 16u * (wave * kWaveSize + lane);
         __syncthreads();                                       // every ring is out of use
-        if (kset == 1) {
+        if (kset != 0) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    *reinterpret_cast<__attribute__((address_space(3))) f32x4*>(
-                        static_cast<uintptr_t>(slot0 + (j * MT + mt) * 16 * kWaveSize * WAVES)) = acc[j][mt];
+                    *reinterpret_cast<__attribute__((address_space(3))) f32x4*>(static_cast<uintptr_t>(
+                        lds_all + kset * STAGES * kStageBytes + slot + (j * MT + mt) * 16 * kWaveSize * WAVES)) = acc[j][mt];
         }
         __syncthreads();
-        if (kset == 1) return;
+        if (kset != 0) return;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int s = 1; s < KSPLIT; ++s)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                acc[j][mt] += *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
-                    static_cast<uintptr_t>(slot0 + (j * MT + mt) * 16 * kWaveSize * WAVES));
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[j][mt] += *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(static_cast<uintptr_t>(
+                        lds_all + s * STAGES * kStageBytes + slot + (j * MT + mt) * 16 * kWaveSize * WAVES));
     }
 
     // ---- epilogue: this lane owns, for token m0 + wm*16*MT + 16*mt + col, features n_base + 4j + r
@@ -397,32 +434,40 @@ hipError_t launch_linear_shape(const void* x, const void* w, const void* bias, c
     return hipGetLastError();
 }
 
-// Shape choice from what the host knows (row capacity and N):
-//   * 256 x 256 tiles, two stages, when there are enough of them for well over one round of the
-//     256 CUs (the large tile halves the L2 -> LDS bytes per flop);
-//   * else 128 x 128 tiles with two stages, two work-groups per CU; when the capacity gives at most 128
-//     such tiles (half the CUs idle, the k-loop is a serial chain), the k-loop is split inside the
-//     group: 27.8 against 33.3 us at 1334 x 768 x 3072, but slower once the grid fills the chip
-//     (19.9 against 16.0 us at 1334 x 2304 x 768), hence the limit.  (A four-stage ring for small
-//     grids was measured too and is slower: 28 against 16 us at 1334 x 2304 x 768.)
+// Shape choice from what the host knows (the expected row count -- the capacity unless the caller
+// gave a better estimate --, N, K); times in us on one MI355X, fp16, no epilogue work:
+//   * 256 x 256 tiles (one work-group of eight wavefronts per CU; half the L2 -> LDS bytes per flop of a
+//     128 x 128 tile) when there are enough of them for well over one round of the 256 CUs, or when the
+//     k-loop is long and the tiles fill at least half the chip (12608 x 768 x 3072: 64 against 75);
+//   * 64 x 64 tiles, one wavefront per k-half (two per work-group), when 128 x 128 tiles would leave at
+//     least half the CUs idle: what limits a small problem is how many bytes the chip has in flight, and
+//     four times as many work-groups, each with two rings, keep more of them going
+//     (1334 x 768 x 3072: 19 against 32; 1334 x 768 x 768: 7.9 against 8.7);
+//   * else 128 x 128 tiles, four wavefronts, two work-groups per CU.
+// Rings of three and four stages were measured too: no gain over two except at 1334 x 768 x 3072, where
+// the 64 x 64 shape is faster still.
 template <typename In>
 hipError_t launch_linear_typed(const void* x, const void* w, const void* bias, const void* res, void* y,
-                               int rows_cap, const int32_t* rows_dev, int N, int K, int act, hipStream_t stream) {
-    const int64_t big_tiles = (int64_t)((rows_cap + 255) / 256) * (N / 256);
-    if (N % 256 == 0 && big_tiles >= kBigTileMinGroups)
+                               int rows_cap, const int32_t* rows_dev, int rows_hint, int N, int K, int act,
+                               hipStream_t stream) {
+    const int ksteps = K / kTK;
+    const int64_t big_tiles = (int64_t)((rows_hint + 255) / 256) * (N / 256);
+    if (N % 256 == 0 && (big_tiles >= kBigTileMinGroups || (ksteps >= 32 && big_tiles >= 128)))
         return launch_linear_shape<In, 4, 2, 8, 2, 1>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
-    const int64_t small_tiles = (int64_t)((rows_cap + 127) / 128) * (N / 128);
-    if (small_tiles <= kSplitMaxGroups && (K / kTK) % 2 == 0 && K / kTK >= 4)
-        return launch_linear_shape<In, 2, 2, 4, 2, 2>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
+    const int64_t small_tiles = (int64_t)((rows_hint + 127) / 128) * (N / 128);
+    if (small_tiles <= kSplitMaxGroups && ksteps % 2 == 0)
+        return launch_linear_shape<In, 1, 1, 4, 2, 2>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
     return launch_linear_shape<In, 2, 2, 4, 2, 1>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
 }
 
 }  // namespace
 
 hipError_t launch_linear(const void* x, const void* w, const void* bias, const void* res, void* y, int rows_cap,
-                         const int32_t* rows_dev, int N, int K, int act, ragged_dtype dt, hipStream_t stream) {
-    if (dt == RAGGED_F16) return launch_linear_typed<F16>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
-    return launch_linear_typed<BF16>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
+                         const int32_t* rows_dev, int rows_hint, int N, int K, int act, ragged_dtype dt,
+                         hipStream_t stream) {
+    if (dt == RAGGED_F16)
+        return launch_linear_typed<F16>(x, w, bias, res, y, rows_cap, rows_dev, rows_hint, N, K, act, stream);
+    return launch_linear_typed<BF16>(x, w, bias, res, y, rows_cap, rows_dev, rows_hint, N, K, act, stream);
 }
 
 int layernorm_max_width() { return kWaveSize * kLnChunks * 8; }

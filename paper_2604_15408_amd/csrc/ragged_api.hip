@@ -7,7 +7,7 @@
 
 namespace {
 
-constexpr int kVersion = 600;  // 0.6.0
+constexpr int kVersion = 700;  // 0.7.0
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_BF16; }
@@ -135,15 +135,17 @@ int ragged_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int
 }
 
 int ragged_linear(const void* x, const void* w, const void* bias, const void* residual, void* y,
-                  int64_t rows_cap, const int32_t* rows_dev, int N, int K, int act, ragged_dtype dt,
-                  void* stream) {
+                  int64_t rows_cap, const int32_t* rows_dev, int64_t rows_hint, int N, int K, int act,
+                  ragged_dtype dt, void* stream) {
     if (!x || !w || !y) return RAGGED_ERR_NULL;
+    if (rows_hint < 0 || rows_hint > rows_cap) return RAGGED_ERR_SHAPE;
     if (rows_cap < 1 || rows_cap > (int64_t)INT32_MAX - 256 || N <= 0 || K <= 0 || K > (1 << 22)) return RAGGED_ERR_SHAPE;
     if (rows_cap * (int64_t)(N / 128 + 1) > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;    // 32-bit grid
     if (!is16bit(dt) || (N % 128) != 0 || (K % 64) != 0 || (act != 0 && act != 1)) return RAGGED_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(residual))
         return RAGGED_ERR_UNSUPPORTED;
-    return from_hip(ragged::launch_linear(x, w, bias, residual, y, (int)rows_cap, rows_dev, N, K, act, dt,
+    return from_hip(ragged::launch_linear(x, w, bias, residual, y, (int)rows_cap, rows_dev,
+                                          (int)(rows_hint > 0 ? rows_hint : rows_cap), N, K, act, dt,
                                           static_cast<hipStream_t>(stream)));
 }
 

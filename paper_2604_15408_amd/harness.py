@@ -279,10 +279,12 @@ class PackedBlocks:
     launch takes the packed row count from cu_seqlens[B] on the device, so the loop is capturable
     and its cost follows the number of kept tokens."""
 
-    def __init__(self, w, depth: int = 8, shared_weights: bool = True, rows_cap: int | None = None):
+    def __init__(self, w, depth: int = 8, shared_weights: bool = True, rows_cap: int | None = None,
+                 rows_hint: int = 0):
         """rows_cap: row capacity of the packed buffers.  B*N always works; a pruning method that keeps a
         fixed number of tokens per image knows T on the host and can pass it, which lets the linear
-        layers size their grids and pick their tiles for the real row count."""
+        layers size their grids for the real row count.  rows_hint: the expected number of kept rows
+        (keep ratio * B * N) when only that is known; the linear layers pick their tile shape from it."""
         import torch
         from paper_2604_15408_amd import binding
         from paper_2604_15408_amd import workloads as wl
@@ -292,7 +294,7 @@ class PackedBlocks:
         cap = B * N if rows_cap is None else int(rows_cap)
         if cap < w.T:
             raise ValueError("rows_cap is smaller than the number of kept tokens")
-        self.cap, self.hidden = cap, 4 * C
+        self.cap, self.hidden, self.rows_hint = cap, 4 * C, int(rows_hint)
         tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
         self.x_in = w.features().to(dev)
         self.keep = w.keep.to(dev)
@@ -309,15 +311,15 @@ class PackedBlocks:
         torch.cuda.synchronize()
 
     def block(self, p):
-        b, w, rows = self.b, self.w, self.rows
+        b, w, rows, hint = self.b, self.w, self.rows, self.rows_hint
         C = w.C
         b.ragged_layernorm(self.x, p["ln1_g"], p["ln1_b"], self.h, rows, LN_EPS)
-        b.ragged_linear(self.h, p["w_qkv"], p["b_qkv"], None, self.qkv.view(self.cap, 3 * C), rows)
+        b.ragged_linear(self.h, p["w_qkv"], p["b_qkv"], None, self.qkv.view(self.cap, 3 * C), rows, rows_hint=hint)
         b.ragged_attn_strided(self.qkv[:, 0], self.qkv[:, 1], self.qkv[:, 2], self.a, self.cu, w.N, w.scale)
-        b.ragged_linear(self.a.view(self.cap, C), p["w_o"], p["b_o"], self.x, self.x, rows)
+        b.ragged_linear(self.a.view(self.cap, C), p["w_o"], p["b_o"], self.x, self.x, rows, rows_hint=hint)
         b.ragged_layernorm(self.x, p["ln2_g"], p["ln2_b"], self.h, rows, LN_EPS)
-        b.ragged_linear(self.h, p["w_fc1"], p["b_fc1"], None, self.mid, rows, "gelu")
-        b.ragged_linear(self.mid, p["w_fc2"], p["b_fc2"], self.x, self.x, rows)
+        b.ragged_linear(self.h, p["w_fc1"], p["b_fc1"], None, self.mid, rows, "gelu", rows_hint=hint)
+        b.ragged_linear(self.mid, p["w_fc2"], p["b_fc2"], self.x, self.x, rows, rows_hint=hint)
 
     def run(self):
         self.b.ragged_pack(self.x_in, self.keep, self.x, self.cu, self.gidx)

@@ -98,11 +98,15 @@ def stay_packed_case(torch):
             "tokens_per_s": pipe.tokens / (wall_graph * 1e-6)}
 
 
-def late_blocks_case(torch, w, label: str, depth: int = 8, tight_cap: bool = False):
+def late_blocks_case(torch, w, label: str, depth: int = 8, tight_cap: bool = False, keep_prob: float | None = None):
     """pack + `depth` encoder blocks on the packed rows + CLS read, in one HIP graph, next to the same
-    blocks over all B*N rows (what a padded pipeline computes)."""
+    blocks over all B*N rows (what a padded pipeline computes).  keep_prob: the pruning ratio the caller
+    configured; the expected row count B * (1 + (N-1) * keep_prob) goes to the linear layers as a hint."""
+    hint = 0 if keep_prob is None else int(round(w.B * (1 + (w.N - 1) * keep_prob)))
+
     def timed(workload):
-        pb = PackedBlocks(workload, depth, rows_cap=workload.T if tight_cap else None)
+        pb = PackedBlocks(workload, depth, rows_cap=workload.T if tight_cap else None,
+                          rows_hint=hint if workload is w else 0)
         pb.run()
         torch.cuda.synchronize()
         g = capture(torch, pb.run)
@@ -111,7 +115,7 @@ def late_blocks_case(torch, w, label: str, depth: int = 8, tight_cap: bool = Fal
     pb, gpu_us, wall_us = timed(w)
     full = wl.deit_b_pruned(1.0, w.B, w.dtype, w.seed) if w.N == 197 else None
     rec = {"case": label, "workload": w.name, "B": w.B, "N": w.N, "T": w.T, "depth": depth,
-           "rows_cap": w.T if tight_cap else w.B * w.N,
+           "rows_cap": w.T if tight_cap else w.B * w.N, "rows_hint": hint,
            "kernels_in_graph": pb.launches, "graph_gpu_us": gpu_us, "graph_wall_us": wall_us,
            "us_per_block": gpu_us / depth, "tflops": pb.flops() / gpu_us / 1e6,
            "tokens_per_s": w.T * depth / (wall_us * 1e-6), "images_per_s_through_late_blocks": w.B / (wall_us * 1e-6)}
@@ -182,10 +186,10 @@ def main():
         emit(pipeline_case(torch))
         emit(stay_packed_case(torch))
     if want("late_blocks"):
-        emit(late_blocks_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "late_blocks_headline"))
+        emit(late_blocks_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "late_blocks_headline", keep_prob=0.2))
         # a fixed number of kept tokens per image: T is known on the host and is the row capacity
         emit(late_blocks_case(torch, wl.uniform(32, 40), "late_blocks_uniform40_tight_cap", tight_cap=True))
-        emit(late_blocks_case(torch, wl.deit_b_pruned(0.5, 8, "f16", 1005), "late_blocks_bs8_keep0.5"))
+        emit(late_blocks_case(torch, wl.deit_b_pruned(0.5, 8, "f16", 1005), "late_blocks_bs8_keep0.5", keep_prob=0.5))
         emit(late_blocks_case(torch, wl.deit_b_pruned(1.0, 64, "f16", 1006), "late_blocks_bs64_dense"))
     if args.out:
         os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)

@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() >= 600
+    assert binding.version() >= 700
     assert binding.status_string(0) == "ok"
     texts = {binding.status_string(s) for s in range(6)}
     assert len(texts) == 6 and binding.status_string(99) == "unknown"
@@ -143,11 +143,12 @@ def test_pack_attn_unpack_validation(lib):
 
 
 def test_linear_validation(lib):
-    def call(x=FAKE, w=FAKE, b=FAKE, r=None, y=FAKE, rows=16, rd=None, N=128, K=64, act=0, dt=0):
-        return lib.ragged_linear(x, w, b, r, y, rows, rd, N, K, act, dt, None)
+    def call(x=FAKE, w=FAKE, b=FAKE, r=None, y=FAKE, rows=16, rd=None, hint=0, N=128, K=64, act=0, dt=0):
+        return lib.ragged_linear(x, w, b, r, y, rows, rd, hint, N, K, act, dt, None)
     for null in ("x", "w", "y"):
         assert call(**{null: None}) == 1
-    for bad in (dict(rows=0), dict(N=0), dict(K=-64), dict(K=(1 << 22) + 64), dict(rows=1 << 31)):
+    for bad in (dict(rows=0), dict(N=0), dict(K=-64), dict(K=(1 << 22) + 64), dict(rows=1 << 31),
+                dict(hint=-1), dict(hint=17)):
         assert call(**bad) == 2
     for bad in (dict(N=192), dict(K=96), dict(act=2), dict(dt=2), dict(x=FAKE + 2), dict(b=FAKE + 8), dict(r=FAKE + 4)):
         assert call(**bad) == 3

@@ -23,7 +23,7 @@ def _rand(shape, seed, dtype, scale=1.0):
     return (torch.randn(*shape, generator=g) * scale).to(dtype)
 
 
-def check_linear(M, N, K, dtype="f16", act="none", bias=True, residual=False, rows=None, cap=None, seed=0):
+def check_linear(M, N, K, dtype="f16", act="none", bias=True, residual=False, rows=None, cap=None, seed=0, hint=0):
     tdt = _TD[dtype]
     cap = M if cap is None else cap
     x = _rand((cap, K), 10 + seed, tdt)
@@ -33,7 +33,7 @@ def check_linear(M, N, K, dtype="f16", act="none", bias=True, residual=False, ro
     y = torch.full((cap, N), 77.0, dtype=tdt, device=DEV)
     rows_dev = None if rows is None else torch.tensor([rows], dtype=torch.int32, device=DEV)
     binding.ragged_linear(x.to(DEV), w.to(DEV), None if b is None else b.to(DEV), None if r is None else r.to(DEV),
-                          y, rows_dev, act)
+                          y, rows_dev, act, rows_hint=hint)
     torch.cuda.synchronize()
     live = cap if rows is None else min(rows, cap)
     got = y.cpu()
@@ -72,6 +72,20 @@ def test_linear_device_row_count():
     check_linear(640, 256, 128, rows=128)
     check_linear(640, 256, 128, rows=513)
     check_linear(640, 256, 128, rows=5000)                      # larger than the capacity: the capacity wins
+
+
+@pytest.mark.parametrize("dtype,act,residual", [("f16", "none", False), ("bf16", "gelu", True)])
+def test_linear_every_launch_shape(dtype, act, residual):
+    """The launch shape follows the expected row count (the capacity, or the caller's hint): 256 x 256
+    tiles for many rows or a long k-loop, 64 x 64 tiles with the k-loop split in two for few rows, 128 x 128
+    tiles between.  Large capacities with a small device row count keep the oracle's work small."""
+    kw = dict(dtype=dtype, act=act, residual=residual)
+    check_linear(700, 1024, 256, rows=700, cap=26000, seed=5, **kw)               # 408 tiles of 256 x 256
+    check_linear(300, 1024, 2048, rows=300, cap=8200, seed=6, **kw)               # long k-loop, 132 such tiles
+    check_linear(700, 1024, 256, rows=700, cap=26000, seed=5, hint=3000, **kw)    # 192 tiles of 128 x 128
+    check_linear(700, 1024, 256, rows=700, cap=26000, seed=5, hint=700, **kw)     # 64 x 64 tiles, k split
+    check_linear(130, 128, 3072, seed=7, **kw)                                    # 64 x 64 tiles, 24 k-steps per half
+    check_linear(700, 1024, 192, rows=650, cap=800, seed=8, hint=650, **kw)       # odd number of k-steps: no split
 
 
 def test_linear_residual_in_place_and_gelu_tails():
