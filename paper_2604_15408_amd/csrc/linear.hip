@@ -35,17 +35,19 @@ constexpr int kTK = 64;                          // contraction elements per sta
 constexpr int kBigTileMinGroups = 400;           // use 256 x 256 tiles from this many of them on
 constexpr int kSplitMaxGroups = 128;             // 64 x 64 tiles with the k-loop split in the group up to this many 128 x 128 tiles
 
-// GELU(t) = t * Phi(t) with Phi from erfc(z) ~ poly(u) * exp(-z^2), u = 1 / (1 + p z), z = |t| / sqrt 2.
+// GELU(t) = t * Phi(t) = max(t, 0) - |t| * erfc(|t| / sqrt 2) / 2, with erfc(z) ~ poly(u) * exp(-z^2),
+// u = 1 / (1 + p z) (Abramowitz-Stegun 7.1.26).  In this form nothing cancels in the negative tail, the
+// halving sits in the coefficients and |t| is an operand modifier: 11 VALU + 2 transcendental ops.
 __device__ __forceinline__ float gelu_erf(float t) {
-    const float z = fabsf(t) * 0.70710678118654752f;
-    const float u = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
-    float poly = __builtin_fmaf(u, 1.061405429f, -1.453152027f);
-    poly = __builtin_fmaf(poly, u, 1.421413741f);
-    poly = __builtin_fmaf(poly, u, -0.284496736f);
-    poly = __builtin_fmaf(poly, u, 0.254829592f);
-    const float half_erfc = 0.5f * poly * u * __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);
-    const float phi = t < 0.f ? half_erfc : 1.0f - half_erfc;     // Phi(t) = erfc(-t / sqrt 2) / 2
-    return t * phi;
+    const float at = fabsf(t);
+    const float u = __builtin_amdgcn_rcpf(__builtin_fmaf(at, 0.3275911f * 0.70710678118654752f, 1.0f));
+    float poly = __builtin_fmaf(u, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+    poly = __builtin_fmaf(poly, u, 0.5f * 1.421413741f);
+    poly = __builtin_fmaf(poly, u, 0.5f * -0.284496736f);
+    poly = __builtin_fmaf(poly, u, 0.5f * 0.254829592f);
+    const float s = at * 0.84932180028801904f;                    // sqrt(log2(e) / 2): exp(-t^2 / 2) = 2^(-s^2)
+    const float half_erfc = poly * u * __builtin_amdgcn_exp2f(-s * s);
+    return __builtin_fmaf(-at, half_erfc, fmaxf(t, 0.f));
 }
 
 __device__ __forceinline__ void unpack16(F16, const uint4& a, const uint4& b, float (&v)[16]) {

@@ -3,7 +3,7 @@
     python -m paper_2604_15408_amd.suite [--out gpurun_out/suite.jsonl]
 
 Cases (each with the step issued as three launches and as the single ragged_pack_attn_unpack launch):
-the headline batch; the bf16 pruning-ratio sweep next to a padded baseline of the same shape
+the headline batch (also with cold caches: many buffer sets in rotation); the bf16 pruning-ratio sweep next to a padded baseline of the same shape
 (this library's own attention kernel run with every image at the full N tokens -- the bytes and
 flops a padded dense attention has to spend, with no mask cost added); the 384x384 serving batches;
 the 12-layer progressive-pruning loop captured in ONE HIP graph, both through the padded tensor every
@@ -56,6 +56,35 @@ def case(torch, w, label: str):
             "step_us": {"hipgraph": step_graph, "eager_prepared": step_lean, "one_launch_prepared": one_wall},
             "one_launch_kernel_us": one_us,
             "step_tokens_per_s": w.T / (min(step_graph, step_lean, one_wall) * 1e-6)}
+
+
+def cold_case(torch, w, label: str, sets: int):
+    """The step and the attention kernel with caches that hold none of their data: `sets` copies of every
+    buffer, used one after the other inside one graph, so that by the time a copy comes round again the
+    other copies have pushed it out of the L2s and the 256 MB Infinity Cache.  (The other cases re-launch
+    on the same buffers.)"""
+    paths = [Path(w, 0) for _ in range(sets)]
+    touched = paths[0].algorithmic()["pack_attn_unpack"]["bytes"]
+
+    def all_steps():
+        for p in paths:
+            p.one_launch()
+
+    def all_attn():
+        for p in paths:
+            p.attn()
+    all_steps()
+    torch.cuda.synchronize()
+    us_step = event_time_us(torch, capture(torch, all_steps).replay, iters=20)[0] / sets
+    us_attn = event_time_us(torch, capture(torch, all_attn).replay, iters=20)[0] / sets
+    warm = paths[0]
+    us_step_warm = event_time_us(torch, capture(torch, warm.one_launch, sets).replay, iters=20)[0] / sets
+    us_attn_warm = event_time_us(torch, capture(torch, warm.attn, sets).replay, iters=20)[0] / sets
+    return {"case": label, "workload": w.name, "T": w.T, "buffer_sets": sets,
+            "touched_mb_all_sets": touched * sets / 1e6,
+            "one_launch_us": {"cold": us_step, "warm": us_step_warm},
+            "attn_us": {"cold": us_attn, "warm": us_attn_warm},
+            "cold_step_tokens_per_s": w.T / (us_step * 1e-6)}
 
 
 def padded_baseline(torch, w):
@@ -164,6 +193,9 @@ def main():
 
     if want("headline"):
         emit(case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "headline"))
+    if want("cold"):
+        emit(cold_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "cold_headline", sets=32))
+        emit(cold_case(torch, wl.pipeline()[0], "cold_dense_bs64", sets=6))
     if want("uniform"):
         emit(case(torch, wl.uniform(32, 40), "uniform_lengths"))        # the paper's BS=32, 40 tok/img row
         emit(case(torch, wl.uniform(1, 40), "uniform_lengths"))
