@@ -140,6 +140,30 @@ def event_time_us(torch, launch, iters: int, warmup: int = 5):
     return statistics.median(samples), statistics.fmean(samples)
 
 
+class StreamedSteps:
+    """Independent steps in flight on several HIP streams (default priority): one set of device buffers
+    and one pre-marshalled ragged_pack_attn_unpack call per stream, issued round-robin.  A step is
+    latency-bound (a 6 us kernel on a chip it cannot fill), so steps of different batches overlap on the
+    GPU; every step still produces all of its outputs in its own buffers."""
+
+    def __init__(self, w, fill_mode: int = 0, streams: int = 3, first: "Path | None" = None):
+        import torch
+        self.paths = ([first] if first is not None else []) + \
+                     [Path(w, fill_mode) for _ in range(streams - (first is not None))]
+        self.streams = [torch.cuda.Stream() for _ in range(streams)]
+        self.calls = []
+        for st, p in zip(self.streams, self.paths):
+            st.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(st):
+                self.calls.append(p.prepared_one_launch())
+        import itertools
+        nxt = itertools.cycle(self.calls).__next__
+
+        def step():                                    # as little host work per step as Python allows
+            nxt()()
+        self.step = step
+
+
 def wall_steps(torch, fn, steps: int):
     torch.cuda.synchronize()
     t0 = time.perf_counter()

@@ -196,3 +196,28 @@ def test_prepared_calls_reproduce_checked_calls():
     torch.cuda.synchronize()
     assert torch.equal(y1, y2) and torch.equal(n1, n2) and torch.equal(c1, c2) and torch.equal(o1, o2)
     assert all(torch.equal(a, b) for a, b in zip(*outs))
+
+
+def test_steps_on_three_streams_fill_every_buffer_set():
+    """The benchmark's multi-stream mode: steps issued round-robin on three streams, each with its own
+    buffers, leave in every buffer set exactly what a single step leaves."""
+    from paper_2604_15408_amd.harness import Path, StreamedSteps
+    w = wl.deit_b_pruned(0.25, B=9, seed=4)
+    ref = Path(w, fill_mode=1)
+    ref.one_launch()
+    torch.cuda.synchronize()
+    ms = StreamedSteps(w, fill_mode=1, streams=3)
+    for p in ms.paths:
+        for n in ("packed", "o", "out"):
+            getattr(p, n).fill_(float("nan"))
+        p.cu.fill_(-1)
+    torch.cuda.synchronize()
+    for _ in range(7):                                  # 7 steps: sets 0, 1, 2, 0, 1, 2, 0
+        ms.step()
+    torch.cuda.synchronize()
+    T = w.T
+    for p in ms.paths:
+        assert torch.equal(p.cu, ref.cu) and torch.equal(p.gidx[:T], ref.gidx[:T])
+        for n in ("packed", "o"):
+            assert torch.equal(getattr(p, n)[:T].view(torch.int16), getattr(ref, n)[:T].view(torch.int16)), n
+        assert torch.equal(p.out.view(torch.int16), ref.out.view(torch.int16))
