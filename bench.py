@@ -69,7 +69,7 @@ def run(args):
     p = Path(w, args.fill_mode)
     alg = p.algorithmic()
 
-    # ---- whole path (every output of pack, attn and unpack), issued in five ways:
+    # ---- whole path (every output of pack, attn and unpack), issued in six ways:
     #   hipgraph            one hipGraphLaunch of the captured three-kernel pipeline
     #   eager               three checked binding calls (tensor checks + marshalling every call)
     #   eager_prepared      three calls with pre-marshalled arguments

@@ -369,6 +369,18 @@ void layernorm_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict
     if (row >= rows) return;
     const int chunks = C / 8;
     const uint4* src = reinterpret_cast<const uint4*>(x + (int64_t)row * C);
+    // every load of the kernel is issued up front (the row, and the scale / shift vectors the last
+    // pass needs), so the two reductions run while gamma and beta are still on their way
+    uint4 raw_x[kLnChunks], raw_g[kLnChunks], raw_b[kLnChunks];
+#pragma unroll
+    for (int i = 0; i < kLnChunks; ++i) {
+        const int c = lane + kWaveSize * i;
+        if (c < chunks) {
+            raw_x[i] = src[c];
+            raw_g[i] = reinterpret_cast<const uint4*>(gamma)[c];
+            raw_b[i] = reinterpret_cast<const uint4*>(beta)[c];
+        }
+    }
     float v[kLnChunks][8];
     float sum = 0.f;
 #pragma unroll
@@ -376,7 +388,7 @@ void layernorm_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict
         const int c = lane + kWaveSize * i;
         if (c < chunks) {
             float t[16];
-            const uint4 raw = src[c];
+            const uint4 raw = raw_x[i];
             unpack16(In{}, raw, raw, t);
 #pragma unroll
             for (int e = 0; e < 8; ++e) { v[i][e] = t[e]; sum += t[e]; }
@@ -399,8 +411,7 @@ void layernorm_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict
         const int c = lane + kWaveSize * i;
         if (c < chunks) {
             float gm[16], bt[16], o16[16];
-            const uint4 graw = reinterpret_cast<const uint4*>(gamma)[c];
-            const uint4 braw = reinterpret_cast<const uint4*>(beta)[c];
+            const uint4 graw = raw_g[i], braw = raw_b[i];
             unpack16(In{}, graw, graw, gm);
             unpack16(In{}, braw, braw, bt);
 #pragma unroll
