@@ -9,7 +9,7 @@ flops a padded dense attention has to spend, with no mask cost added); the 384x3
 the 12-layer progressive-pruning loop captured in ONE HIP graph, both through the padded tensor every
 layer (36 kernels) and staying packed (17 kernels); eight packed encoder blocks ("late blocks": LayerNorm,
 QKV projection, ragged attention, output projection, MLP with GELU, residuals) with synthetic weights,
-next to the same blocks over all B*N rows.  Kernel times are HIP-event times
+next to the same blocks over all B*N rows, and with three independent batches in flight on three streams.  Kernel times are HIP-event times
 of a graph holding 20 back-to-back copies of the kernel (divided by 20), so they include the
 in-graph kernel-to-kernel gap that an empty kernel shows separately.
 """
@@ -155,6 +155,32 @@ def late_blocks_case(torch, w, label: str, depth: int = 8, tight_cap: bool = Fal
     return rec
 
 
+def late_blocks_in_flight_case(torch, w, label: str, batches: int, keep_prob: float, depth: int = 8):
+    """Several independent batches in flight: one PackedBlocks graph per batch, each replayed on its own
+    HIP stream (default priority).  At a few thousand rows every kernel of the block is bound by latency
+    and leaves most of the chip idle, so kernels of different batches overlap."""
+    hint = int(round(w.B * (1 + (w.N - 1) * keep_prob)))
+    pbs = [PackedBlocks(w, depth, rows_hint=hint) for _ in range(batches)]
+    graphs = []
+    for pb in pbs:
+        pb.run()
+        torch.cuda.synchronize()
+        graphs.append(capture(torch, pb.run))
+    streams = [torch.cuda.Stream() for _ in range(batches)]
+
+    def go():
+        for g, st in zip(graphs, streams):
+            with torch.cuda.stream(st):
+                g.replay()
+    for _ in range(5):
+        go()
+    per_batch = wall_steps(torch, go, 40) / batches
+    one = wall_steps(torch, graphs[0].replay, 40)
+    return {"case": label, "workload": w.name, "B": w.B, "T": w.T, "depth": depth, "batches_in_flight": batches,
+            "wall_us_per_batch": per_batch * 1e6, "wall_us_per_batch_alone": one * 1e6,
+            "images_per_s_through_late_blocks": w.B / per_batch, "tokens_per_s": w.T * depth / per_batch}
+
+
 def mask_producer_case(torch, B: int = 32, N: int = 197, k: int = 40):
     """The keep-mask producer in front of pack: fp64 l2 scores + per-image top-k, then pack."""
     from . import binding
@@ -219,6 +245,8 @@ def main():
         emit(stay_packed_case(torch))
     if want("late_blocks"):
         emit(late_blocks_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "late_blocks_headline", keep_prob=0.2))
+        emit(late_blocks_in_flight_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "late_blocks_headline_3_in_flight",
+                                        batches=3, keep_prob=0.2))
         # a fixed number of kept tokens per image: T is known on the host and is the row capacity
         emit(late_blocks_case(torch, wl.uniform(32, 40), "late_blocks_uniform40_tight_cap", tight_cap=True))
         emit(late_blocks_case(torch, wl.deit_b_pruned(0.5, 8, "f16", 1005), "late_blocks_bs8_keep0.5", keep_prob=0.5))
