@@ -97,6 +97,22 @@ def padded_baseline(torch, w):
     return event_time_us(torch, g.replay, iters=30)[0] / REPLICAS
 
 
+def library_padded_sdpa_us(torch, w):
+    """Context only: the framework's own scaled_dot_product_attention on the padded [B, H, N, D] layout with
+    a boolean key mask built from the keep mask -- what the paper calls the padded baseline.  Eager calls
+    timed with events (the library call may allocate, so it is not captured).  None if the call fails."""
+    try:
+        import torch.nn.functional as F
+        tdt = torch.float16 if w.dtype == "f16" else torch.bfloat16
+        g = torch.Generator(device="cuda:0").manual_seed(1)
+        q, k, v = (torch.randn(w.B, w.H, w.N, w.D, generator=g, device="cuda:0").to(tdt) for _ in range(3))
+        mask = w.keep.to("cuda:0").bool()[:, None, None, :]              # keys of dropped tokens masked out
+        fn = lambda: F.scaled_dot_product_attention(q, k, v, attn_mask=mask, scale=w.scale)
+        return event_time_us(torch, lambda: [fn() for _ in range(10)], iters=20)[0] / 10
+    except Exception:                                                    # noqa: BLE001 - optional context number
+        return None
+
+
 def pipeline_case(torch):
     layers = wl.pipeline()
     pipe = Pipeline(layers, fill_mode=1)
@@ -235,6 +251,7 @@ def main():
             if pad_us is None:
                 pad_us = padded_baseline(torch, w)
             rec["padded_attn_us"] = pad_us
+            rec["library_padded_sdpa_us"] = library_padded_sdpa_us(torch, w)
             rec["attn_speedup_vs_padded"] = pad_us / rec["kernel_us"]["attn"]
             emit(rec)
     if want("serving_384"):
