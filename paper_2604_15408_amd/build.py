@@ -62,7 +62,21 @@ def build(verbose: bool = False, extra_flags=()) -> Path:
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
     os.replace(tmp, LIB)
+    build_call_cost(hipcc)
     return LIB
+
+
+CALL_COST = PKG / "ragged_call_cost"
+
+
+def build_call_cost(hipcc: str) -> Path:
+    """The small C++ program that times the C ABI without Python in the loop (native/call_cost.cpp)."""
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", f"-I{ROOT / 'include'}",
+                          "-o", str(CALL_COST), str(PKG / "native" / "call_cost.cpp"), f"-L{PKG}", "-lragged_hip",
+                          "-Wl,-rpath,$ORIGIN"], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"building ragged_call_cost failed:\n{res.stderr}")
+    return CALL_COST
 
 
 if __name__ == "__main__":
