@@ -357,3 +357,92 @@ class PackedBlocks:
         linear = 2 * T * (3 * C * C + C * C + 2 * C * self.hidden)
         attn = 4 * w.D * w.H * sum(n * n for n in w.lengths)
         return self.depth * (linear + attn)
+
+
+class ProgressiveBlocks:
+    """The whole flow of the paper's Section 4.3 with real blocks: a `depth`-block pre-norm encoder (synthetic
+    weights) that prunes tokens in front of the blocks listed in `prune_at` and never leaves the packed
+    layout.  A pruning stage is three launches -- ragged_token_scores_l2 on the packed rows,
+    ragged_keep_topk (class token plus the k - 1 best others per image, k = round(keep_ratio * n)) and
+    ragged_repack -- so every image keeps the same, host-known number of tokens and each stage's buffers
+    have exactly B * n_s rows; blocks are the seven launches of PackedBlocks; ragged_cls_extract ends the
+    run.  Everything is device-side and capturable in one HIP graph."""
+
+    def __init__(self, B: int, N: int = 197, H: int = 12, D: int = 64, depth: int = 12, prune_at=(3, 6, 9),
+                 keep_ratio: float = 0.7, dtype: str = "f16", seed: int = 3000, shared_weights: bool = True):
+        import torch
+        from paper_2604_15408_amd import binding
+        from paper_2604_15408_amd import workloads as wl
+        self.torch, self.b = torch, binding
+        self.B, self.N, self.H, self.D, self.depth = B, N, H, D, depth
+        self.C = C = H * D
+        self.scale = D ** -0.5
+        self.prune_at = tuple(sorted(prune_at))
+        dev = "cuda:0"
+        tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+        self.lengths = [N]                                     # tokens per image at every stage
+        for _ in self.prune_at:
+            self.lengths.append(max(1, int(round(keep_ratio * self.lengths[-1]))))
+        keep_all = torch.ones(B, N, dtype=torch.uint8)
+        self.input = wl.Workload("progressive_input", B, N, H, D, dtype, seed, keep_all)
+        self.x_in = self.input.features().to(dev)
+        self.keep_all = keep_all.to(dev)
+        z = lambda *shape, dt=tdt: torch.zeros(*shape, dtype=dt, device=dev)
+        self.x = [z(B * n, C) for n in self.lengths]           # packed activations of every stage
+        self.cu = [z(B + 1, dt=torch.int32) for _ in self.lengths]
+        self.gidx = [z(B * n, dt=torch.int32) for n in self.lengths]
+        self.scores = [z(B, n, dt=torch.float64) for n in self.lengths[:-1]]
+        self.keep = [z(B, n, dt=torch.uint8) for n in self.lengths[:-1]]
+        rows0 = B * N
+        self.h, self.qkv, self.a, self.mid = z(rows0, C), z(rows0, 3, H, D), z(rows0, H, D), z(rows0, 4 * C)
+        self.cls = z(B, C)
+        sets = 1 if shared_weights else depth
+        self.params = [{k: v.to(dev) for k, v in wl.block_weights(C, 4 * C, dtype, seed + 1 + i).items()}
+                       for i in range(sets)]
+        self.launches = 1 + 7 * depth + 3 * len(self.prune_at) + 1
+        self.stage = 0
+        torch.cuda.synchronize()
+
+    def pack_all(self):
+        self.stage = 0
+        self.b.ragged_pack(self.x_in, self.keep_all, self.x[0], self.cu[0], self.gidx[0])
+
+    def prune(self):
+        """scores -> top-k keep mask -> re-pack; moves on to the next stage's buffers."""
+        b, s = self.b, self.stage
+        n, k = self.lengths[s], self.lengths[s + 1]
+        b.ragged_token_scores_l2(self.x[s].view(self.B, n, self.C), self.scores[s])
+        b.ragged_keep_topk(self.scores[s], k, self.keep[s])
+        b.ragged_repack(self.x[s], self.keep[s].view(-1), self.cu[s], self.x[s + 1], self.cu[s + 1], self.gidx[s + 1])
+        self.stage = s + 1
+
+    def block(self, p):
+        b, s, C = self.b, self.stage, self.C
+        rows = self.B * self.lengths[s]
+        x, cu = self.x[s], self.cu[s]
+        rows_dev = cu[self.B:]
+        h, qkv, a, mid = self.h[:rows], self.qkv[:rows], self.a[:rows], self.mid[:rows]
+        b.ragged_layernorm(x, p["ln1_g"], p["ln1_b"], h, rows_dev, LN_EPS)
+        b.ragged_linear(h, p["w_qkv"], p["b_qkv"], None, qkv.view(rows, 3 * C), rows_dev)
+        b.ragged_attn_strided(qkv[:, 0], qkv[:, 1], qkv[:, 2], a, cu, self.lengths[s], self.scale)
+        b.ragged_linear(a.view(rows, C), p["w_o"], p["b_o"], x, x, rows_dev)
+        b.ragged_layernorm(x, p["ln2_g"], p["ln2_b"], h, rows_dev, LN_EPS)
+        b.ragged_linear(h, p["w_fc1"], p["b_fc1"], None, mid, rows_dev, "gelu")
+        b.ragged_linear(mid, p["w_fc2"], p["b_fc2"], x, x, rows_dev)
+
+    def run(self):
+        self.pack_all()
+        for blk in range(self.depth):
+            if blk in self.prune_at:
+                self.prune()
+            self.block(self.params[blk % len(self.params)])
+        self.b.ragged_cls_extract(self.x[self.stage], self.cu[self.stage], self.cls)
+
+    def tokens(self) -> int:
+        """Token-blocks processed in one run (rows summed over the blocks)."""
+        total, s = 0, 0
+        for blk in range(self.depth):
+            if blk in self.prune_at:
+                s += 1
+            total += self.B * self.lengths[s]
+        return total

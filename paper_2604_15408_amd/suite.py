@@ -21,7 +21,7 @@ import os
 import sys
 
 from . import workloads as wl
-from .harness import (REPLICAS, PackedBlocks, PaddedPath, Path, Pipeline, StayPackedPipeline, capture,
+from .harness import (REPLICAS, PackedBlocks, PaddedPath, Path, Pipeline, ProgressiveBlocks, StayPackedPipeline, capture,
                       event_time_us, wall_steps)
 
 
@@ -197,6 +197,24 @@ def late_blocks_in_flight_case(torch, w, label: str, batches: int, keep_prob: fl
             "images_per_s_through_late_blocks": w.B / per_batch, "tokens_per_s": w.T * depth / per_batch}
 
 
+def progressive_case(torch, B: int, label: str):
+    """A 12-block DeiT-B-shaped encoder that prunes to 70 % by top-k l2 score in front of blocks 3, 6 and 9
+    (197 -> 138 -> 97 -> 68 tokens per image) and stays packed throughout, in one HIP graph; next to the same
+    12 blocks without pruning."""
+    def timed(prune_at):
+        pb = ProgressiveBlocks(B=B, depth=12, prune_at=prune_at, keep_ratio=0.7)
+        pb.run()
+        torch.cuda.synchronize()
+        g = capture(torch, pb.run)
+        return pb, event_time_us(torch, g.replay, iters=10)[0], wall_steps(torch, g.replay, 20) * 1e6
+    pb, gpu_us, wall_us = timed((3, 6, 9))
+    _, dense_us, _ = timed(())
+    return {"case": label, "B": B, "N": pb.N, "tokens_per_image": pb.lengths, "kernels_in_graph": pb.launches,
+            "graph_gpu_us": gpu_us, "graph_wall_us": wall_us, "unpruned_graph_gpu_us": dense_us,
+            "speedup_vs_unpruned": dense_us / gpu_us, "token_blocks": pb.tokens(),
+            "images_per_s": B / (wall_us * 1e-6)}
+
+
 def mask_producer_case(torch, B: int = 32, N: int = 197, k: int = 40):
     """The keep-mask producer in front of pack: fp64 l2 scores + per-image top-k, then pack."""
     from . import binding
@@ -268,6 +286,9 @@ def main():
         emit(late_blocks_case(torch, wl.uniform(32, 40), "late_blocks_uniform40_tight_cap", tight_cap=True))
         emit(late_blocks_case(torch, wl.deit_b_pruned(0.5, 8, "f16", 1005), "late_blocks_bs8_keep0.5", keep_prob=0.5))
         emit(late_blocks_case(torch, wl.deit_b_pruned(1.0, 64, "f16", 1006), "late_blocks_bs64_dense"))
+    if want("progressive"):
+        emit(progressive_case(torch, 32, "progressive_12_blocks_bs32"))
+        emit(progressive_case(torch, 8, "progressive_12_blocks_bs8"))
     if args.out:
         os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
         with open(args.out, "w") as f:

@@ -1,0 +1,90 @@
+"""GPU check of harness.ProgressiveBlocks -- the flow of the paper's Section 4.3 with real blocks: pack once,
+run encoder blocks on the packed rows, prune by top-k l2 score (scores -> keep mask -> re-pack) without ever
+leaving the packed layout, read the class tokens at the end.  Every pruning stage is compared with the CPU
+oracle applied to the GPU's own input of that stage (so the rounding of the blocks before it is not compared
+twice); the blocks themselves have their stage-by-stage parity test in test_gpu_block.py."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_15408_amd import workloads as wl
+from paper_2604_15408_amd.harness import ProgressiveBlocks, capture
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+def make():
+    return ProgressiveBlocks(B=3, N=40, H=2, D=64, depth=3, prune_at=(1, 2), keep_ratio=0.6, seed=77)
+
+
+def test_every_pruning_stage_against_the_oracle():
+    pb = make()
+    B, C = pb.B, pb.C
+    assert pb.lengths == [40, 24, 14] and pb.launches == 1 + 21 + 6 + 1
+    pb.pack_all()
+    torch.cuda.synchronize()
+    assert pb.cu[0].cpu().tolist() == [0, 40, 80, 120]
+    assert torch.equal(pb.x[0].view(torch.int16), pb.x_in.view(B * 40, C).view(torch.int16))
+    for blk in range(pb.depth):
+        if blk in pb.prune_at:
+            s = pb.stage
+            n, k = pb.lengths[s], pb.lengths[s + 1]
+            before = wl.to_words(pb.x[s].cpu())                            # the stage's input as the GPU holds it
+            pb.prune()
+            torch.cuda.synchronize()
+            want_scores = oracle.scores_l2(before.reshape(B, n, C))
+            assert np.allclose(pb.scores[s].cpu().numpy(), want_scores, rtol=1e-14, atol=0)
+            want_keep = oracle.keep_topk(want_scores, k)
+            assert np.array_equal(pb.keep[s].cpu().numpy(), want_keep)
+            want_rows, want_cu, want_gi = oracle.repack(before, want_keep.reshape(-1), hp.cu_from_lengths([n] * B))
+            assert want_cu.tolist() == [i * k for i in range(B + 1)]       # every image keeps exactly k tokens
+            assert np.array_equal(pb.cu[s + 1].cpu().numpy(), want_cu)
+            assert np.array_equal(pb.gidx[s + 1].cpu().numpy(), want_gi)
+            assert np.array_equal(wl.to_words(pb.x[s + 1].cpu()), want_rows)
+            assert np.all(want_gi[::k] == np.arange(B) * n)                # the class token leads every image
+        pb.block(pb.params[0])
+    pb.b.ragged_cls_extract(pb.x[pb.stage], pb.cu[pb.stage], pb.cls)
+    torch.cuda.synchronize()
+    last = wl.to_words(pb.x[pb.stage].cpu())
+    assert np.array_equal(wl.to_words(pb.cls.cpu()), oracle.cls_extract(last, hp.cu_from_lengths([pb.lengths[-1]] * B)))
+    assert torch.isfinite(pb.cls.float()).all()
+
+
+def test_run_is_reproducible_and_graph_replays_match_eager():
+    pb = make()
+    pb.run()
+    torch.cuda.synchronize()
+    want = pb.cls.clone()
+    want_keep = [k.clone() for k in pb.keep]
+    pb.run()
+    torch.cuda.synchronize()
+    assert torch.equal(pb.cls.view(torch.int16), want.view(torch.int16))
+    g = capture(torch, pb.run)
+    for _ in range(3):
+        pb.cls.zero_()
+        for k in pb.keep:
+            k.zero_()
+        for x in pb.x:
+            x.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(pb.cls.view(torch.int16), want.view(torch.int16))
+        assert all(torch.equal(a, b) for a, b in zip(pb.keep, want_keep))
+
+
+def test_deit_b_shape_runs_and_keeps_class_tokens():
+    """Full-width blocks (C = 768) on a small batch: lengths 197 -> 138 -> 97 -> 68, class tokens survive."""
+    pb = ProgressiveBlocks(B=2, depth=12, prune_at=(3, 6, 9), keep_ratio=0.7, seed=5)
+    assert pb.lengths == [197, 138, 97, 68] and pb.launches == 95
+    pb.run()
+    torch.cuda.synchronize()
+    assert pb.cu[3].cpu().tolist() == [0, 68, 136]
+    assert torch.isfinite(pb.cls.float()).all()
+    # composed gather indices lead back to token 0 of every image
+    src = pb.gidx[3][pb.cu[3][:2].long()].long()
+    src = pb.gidx[2][src].long()
+    src = pb.gidx[1][src].long()
+    assert src.cpu().tolist() == [0, 197]
