@@ -190,7 +190,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (images are independent, so the path "
-              "shards by image with no exchange step; see DESIGN.md); use --gpus 1", file=sys.stderr)
+              "shards by image with no exchange step); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     result = run(args)
     if args.calibrate_copy:

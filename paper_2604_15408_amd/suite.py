@@ -1,6 +1,6 @@
 """Measure every benchmark configuration on one MI355X and print one JSON line per case.
 
-    python -m paper_2604_15408_amd.suite [--out gpurun_out/suite.jsonl]
+    python -m paper_2604_15408_amd.suite [--only CASE] [--out results/suite.jsonl]
 
 Cases (each with the step issued as three launches and as the single ragged_pack_attn_unpack launch):
 the headline batch (also with cold caches: many buffer sets in rotation); the bf16 pruning-ratio sweep next to a padded baseline of the same shape
