@@ -81,18 +81,13 @@ def run(args):
     lean_step = p.prepared_step()
     lean_one = p.prepared_one_launch()
     streamed = StreamedSteps(w, args.fill_mode, streams=3, first=None)
-    for _ in range(args.warmup):
-        g_step.replay()
-        p.step()
-        lean_step()
-        lean_one()
-        streamed.step()
-    t_modes = {"hipgraph": wall_steps(torch, g_step.replay, args.steps),
-               "eager": wall_steps(torch, p.step, args.steps),
-               "eager_prepared": wall_steps(torch, lean_step, args.steps),
-               "one_launch": wall_steps(torch, p.one_launch, args.steps),
-               "one_launch_prepared": wall_steps(torch, lean_one, args.steps),
-               "one_launch_prepared_streams3": wall_steps(torch, streamed.step, args.steps)}
+    issue = {"hipgraph": g_step.replay, "eager": p.step, "eager_prepared": lean_step, "one_launch": p.one_launch,
+             "one_launch_prepared": lean_one, "one_launch_prepared_streams3": streamed.step}
+    t_modes = {}
+    for name, fn in issue.items():                 # every way: W untimed steps of its own, then exactly K timed ones
+        for _ in range(args.warmup):
+            fn()
+        t_modes[name] = wall_steps(torch, fn, args.steps)
     mode = min(t_modes, key=t_modes.get)
     t_step = t_modes[mode]
 

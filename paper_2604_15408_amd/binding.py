@@ -322,6 +322,18 @@ def ragged_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream
     _check("ragged_unpack", st)
 
 
+_UNTYPED = None
+
+
+def _untyped() -> ctypes.CDLL:
+    """A second handle of the library whose functions carry no argument types (see Prepared)."""
+    global _UNTYPED
+    if _UNTYPED is None:
+        load()
+        _UNTYPED = ctypes.CDLL(str(LIB_PATH))
+    return _UNTYPED
+
+
 class Prepared:
     """A call with its arguments marshalled once: ``prepared()`` re-issues the same launch on the
     stream it was prepared for, skipping the per-call tensor checks (serving loops re-launch the same
@@ -331,7 +343,13 @@ class Prepared:
     __slots__ = ("_fn", "_args", "_name", "_keepalive")
 
     def __init__(self, name, fn, args, keepalive):
-        self._name, self._fn, self._args, self._keepalive = name, fn, args, keepalive
+        # The arguments are converted to C values once, with the checked function's own argument types,
+        # and the call goes through an untyped handle of the same symbol: ctypes then has nothing left
+        # to convert per call (1.0 instead of 1.7 us of host time for the 19 arguments of a step).
+        self._name, self._keepalive = name, keepalive
+        self._args = tuple(t(a) for t, a in zip(fn.argtypes, args))
+        self._fn = getattr(_untyped(), name)
+        self._fn.restype = ctypes.c_int
 
     def __call__(self) -> None:
         st = self._fn(*self._args)
