@@ -88,6 +88,35 @@ def test_linear_every_launch_shape(dtype, act, residual):
     check_linear(700, 1024, 192, rows=650, cap=800, seed=8, hint=650, **kw)       # odd number of k-steps: no split
 
 
+@pytest.mark.parametrize("M", [12608, 6304])
+@pytest.mark.parametrize("N,K,act,residual", [(2304, 768, "none", False), (768, 768, "none", True),
+                                               (3072, 768, "gelu", False), (768, 3072, "none", True)])
+def test_linear_layer_shapes_at_full_size_on_sampled_rows(M, N, K, act, residual):
+    """The four linear layers of a DeiT-B block at the row counts the benchmarks run (B*N for B = 64 and 32):
+    the whole launch runs on the GPU, the oracle checks a sample of rows -- the first and last row of the
+    buffer, rows around tile boundaries of every launch shape, and seeded random ones."""
+    tdt = torch.float16
+    x = _rand((M, K), 50, tdt)
+    w = _rand((N, K), 51, tdt, K ** -0.5)
+    b = _rand((N,), 52, tdt, 0.5)
+    r = _rand((M, N), 53, tdt) if residual else None
+    y = torch.full((M, N), 77.0, dtype=tdt, device=DEV)
+    binding.ragged_linear(x.to(DEV), w.to(DEV), b.to(DEV), None if r is None else r.to(DEV), y, None, act)
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(M + N)
+    rows = {0, 1, 63, 64, 127, 128, 255, 256, 257, M // 2, M - 257, M - 256, M - 129, M - 128, M - 65, M - 64, M - 2, M - 1}
+    rows |= {int(v) for v in torch.randint(0, M, (78,), generator=g)}
+    rows = sorted(rows)
+    xs = x[rows]
+    want = oracle.linear(wl.to_words(xs), wl.to_words(w), wl.to_words(b), None if r is None else wl.to_words(r[rows]),
+                         act, "f16", threads=oracle.max_threads())
+    S = oracle.linear(wl.to_words(xs.abs()), wl.to_words(w.abs()), dtype="f16", threads=oracle.max_threads())
+    got = y[rows].cpu().to(torch.float64).numpy()
+    bound = _ULP["f16"] * np.abs(want) + 2.0 ** -15 * S + 1e-6
+    assert np.all(np.abs(got - want) <= bound), float((np.abs(got - want) / bound).max())
+    assert not torch.any(y == 77.0), "some output element was never written"
+
+
 def test_linear_residual_in_place_and_gelu_tails():
     tdt = torch.float16
     M, N, K = 200, 256, 128
