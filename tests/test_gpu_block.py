@@ -117,6 +117,20 @@ def test_linear_layer_shapes_at_full_size_on_sampled_rows(M, N, K, act, residual
     assert not torch.any(y == 77.0), "some output element was never written"
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_linear_random_shapes(seed):
+    """Seeded random problems: rows, capacity, device row count, hint, N, K, epilogue and dtype all vary."""
+    g = torch.Generator().manual_seed(9000 + seed)
+    ri = lambda lo, hi: int(torch.randint(lo, hi + 1, (1,), generator=g))
+    cap = ri(1, 900)
+    rows = [None, ri(0, cap), cap + 5][ri(0, 2)]
+    live = cap if rows is None else min(rows, cap)
+    hint = [0, max(1, live), cap][ri(0, 2)]
+    N, K = 128 * ri(1, 6), 64 * ri(1, 14)
+    check_linear(cap, N, K, dtype=["f16", "bf16"][ri(0, 1)], act=["none", "gelu"][ri(0, 1)], bias=bool(ri(0, 1)),
+                 residual=bool(ri(0, 1)), rows=rows, cap=cap, seed=seed, hint=hint)
+
+
 def test_linear_residual_in_place_and_gelu_tails():
     tdt = torch.float16
     M, N, K = 200, 256, 128
