@@ -80,7 +80,7 @@ def run(args):
     g_step = capture(torch, p.step)
     lean_step = p.prepared_step()
     lean_one = p.prepared_one_launch()
-    streamed = StreamedSteps(w, args.fill_mode, streams=3, first=None)
+    streamed = StreamedSteps(w, args.fill_mode, streams=3)
     issue = {"hipgraph": g_step.replay, "eager": p.step, "eager_prepared": lean_step, "one_launch": p.one_launch,
              "one_launch_prepared": lean_one, "one_launch_prepared_streams3": streamed.step}
     t_modes = {}

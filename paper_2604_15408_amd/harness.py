@@ -140,53 +140,55 @@ def event_time_us(torch, launch, iters: int, warmup: int = 5):
     return statistics.median(samples), statistics.fmean(samples)
 
 
+def pick_streams(torch, n: int, bind, extra: int = 3, burst: int = 300):
+    """n HIP streams (default priority) whose work overlaps, and the step function bound to them.
+    HIP streams share a small number of hardware queues (four per process here) and two streams behind one
+    queue run their kernels one after the other; which streams share is not visible from the API (a burst
+    of empty kernels does not tell them apart either).  So a few more streams than needed are drawn,
+    `bind(selection)` -- which returns a function that issues one step of the caller's real work on the
+    given streams, round-robin -- is timed over a short burst for several selections of n, and the
+    fastest selection is kept.  Returns (streams, step)."""
+    pool = [torch.cuda.Stream() for _ in range(n + extra)]
+    for st in pool:
+        st.wait_stream(torch.cuda.current_stream())
+    selections = [pool[i:i + n] for i in range(len(pool) - n + 1)]
+    if extra > 0 and len(pool) >= 2 * n:
+        selections.append(pool[::2][:n])
+    best = None
+    for sel in selections:
+        step = bind(sel)
+        if len(selections) == 1:
+            return sel, step
+        for _ in range(max(10, burst // 5)):
+            step()
+        t = min(wall_steps(torch, step, burst) for _ in range(2))
+        if best is None or t < best[0]:
+            best = (t, sel, step)
+    return best[1], best[2]
+
+
 class StreamedSteps:
-    """Independent steps in flight on several HIP streams (default priority): one set of device buffers
-    and one pre-marshalled ragged_pack_attn_unpack call per stream, issued round-robin.  A step is
-    latency-bound (a 6 us kernel on a chip it cannot fill), so steps of different batches overlap on the
-    GPU; every step still produces all of its outputs in its own buffers.
+    """Independent steps in flight on several HIP streams (default priority, chosen by pick_streams): one set
+    of device buffers and one pre-marshalled ragged_pack_attn_unpack call per stream, issued round-robin.
+    A step is latency-bound (a 6 us kernel on a chip it cannot fill), so steps of different batches
+    overlap on the GPU; every step still produces all of its outputs in its own buffers."""
 
-    HIP streams share a small number of hardware queues (four per process here), and two streams behind one
-    queue do not overlap.  Which streams share is not visible from the API, so with `tune` the constructor
-    draws a few more streams than it needs, times a short burst on several selections and keeps the best."""
-
-    def __init__(self, w, fill_mode: int = 0, streams: int = 3, first: "Path | None" = None, tune: bool = True):
+    def __init__(self, w, fill_mode: int = 0, streams: int = 3, tune: bool = True):
         import itertools
         import torch
-        self.paths = ([first] if first is not None else []) + \
-                     [Path(w, fill_mode) for _ in range(streams - (first is not None))]
-        pool = [torch.cuda.Stream() for _ in range(streams + 3 if tune else streams)]
-        for st in pool:
-            st.wait_stream(torch.cuda.current_stream())
+        self.paths = [Path(w, fill_mode) for _ in range(streams)]
 
         def bind(selection):
             calls = []
             for st, p in zip(selection, self.paths):
                 with torch.cuda.stream(st):
                     calls.append(p.prepared_one_launch())
-            return calls
-
-        selections = [pool[i:i + streams] for i in range(len(pool) - streams + 1)]
-        if tune and len(pool) >= 2 * streams:
-            selections.append(pool[::2][:streams])
-        best = None
-        for sel in selections:
-            calls = bind(sel)
-            if len(selections) == 1:
-                best = (0.0, sel, calls)
-                break
             nxt = itertools.cycle(calls).__next__
-            for _ in range(60):
-                nxt()()
-            t = min(wall_steps(torch, lambda: nxt()(), 300) for _ in range(2))
-            if best is None or t < best[0]:
-                best = (t, sel, calls)
-        self.streams, self.calls = best[1], best[2]
-        nxt = itertools.cycle(self.calls).__next__
 
-        def step():                                    # as little host work per step as Python allows
-            nxt()()
-        self.step = step
+            def step():                                # as little host work per step as Python allows
+                nxt()()
+            return step
+        self.streams, self.step = pick_streams(torch, streams, bind, extra=3 if tune else 0)
 
 
 def wall_steps(torch, fn, steps: int):

@@ -21,7 +21,7 @@ import os
 import sys
 
 from . import workloads as wl
-from .harness import (REPLICAS, PackedBlocks, PaddedPath, Path, Pipeline, ProgressiveBlocks, StayPackedPipeline, capture,
+from .harness import (REPLICAS, PackedBlocks, PaddedPath, Path, Pipeline, ProgressiveBlocks, StayPackedPipeline, capture, pick_streams,
                       event_time_us, wall_steps)
 
 
@@ -182,12 +182,14 @@ def late_blocks_in_flight_case(torch, w, label: str, batches: int, keep_prob: fl
         pb.run()
         torch.cuda.synchronize()
         graphs.append(capture(torch, pb.run))
-    streams = [torch.cuda.Stream() for _ in range(batches)]
 
-    def go():
-        for g, st in zip(graphs, streams):
-            with torch.cuda.stream(st):
-                g.replay()
+    def bind(selection):
+        def go():
+            for g, st in zip(graphs, selection):
+                with torch.cuda.stream(st):
+                    g.replay()
+        return go
+    _, go = pick_streams(torch, batches, bind, burst=10)
     for _ in range(5):
         go()
     per_batch = wall_steps(torch, go, 40) / batches
