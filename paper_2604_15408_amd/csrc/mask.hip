@@ -6,7 +6,7 @@
 //     not depend on the summation order and ranking decisions agree with any other exact evaluation.
 //   keep_topk_kernel: per image, token 0 (the class token) is kept and, of the others, the k-1 with
 //     the largest score (equal scores: lower position first).  Scores of the image in LDS, an O(N)
-//     count per token split over four lanes -- N is a few hundred.
+//     count per token split over eight lanes -- N is a few hundred.
 #include "common.h"
 #include "mfma_lds.h"
 
@@ -36,28 +36,31 @@ void token_scores_l2_kernel(const uint4* __restrict__ x, int64_t rows, int chunk
     if (lane == 0) scores[row] = acc;
 }
 
-// One work-group per (image, 64 tokens): four lanes share a token and split the range of rivals
-// u = 1 .. N-1 between them (u = part, part+4, ...), so the counting loop is a quarter as long and the
-// image's scores are read from LDS; the four partial counts meet in a quad reduction.
-constexpr int kTopkTokens = kBlockThreads / 4;
+// One work-group per (image, 32 tokens): eight lanes share a token and split the range of rivals
+// u = 1 .. N-1 between them (u = 1 + part, 9 + part, ...), so the counting loop is an eighth as long and
+// the image's scores are read from LDS; the eight partial counts meet in a three-step reduction.
+constexpr int kTopkLanes = 8;
+constexpr int kTopkTokens = kBlockThreads / kTopkLanes;
 
 __global__ __launch_bounds__(kBlockThreads)
 void keep_topk_kernel(const double* __restrict__ scores, int N, int k, int chunks, uint8_t* __restrict__ keep) {
     __shared__ double s[kMaxMaskTokens];
     const int img = blockIdx.x / chunks;
-    const int t = (blockIdx.x - img * chunks) * kTopkTokens + (threadIdx.x >> 2);
-    const int part = threadIdx.x & 3;
+    const int t = (blockIdx.x - img * chunks) * kTopkTokens + threadIdx.x / kTopkLanes;
+    const int part = threadIdx.x % kTopkLanes;
     const double* mine = scores + (int64_t)img * N;
     for (int u = threadIdx.x; u < N; u += kBlockThreads) s[u] = mine[u];
     __syncthreads();
     const double st = s[t < N ? t : 0];
     int before = 0;
-    for (int u = 1 + part; u < N; u += 4) {
+#pragma unroll 4
+    for (int u = 1 + part; u < N; u += kTopkLanes) {
         const double su = s[u];
         before += (u != t && (su > st || (su == st && u < t))) ? 1 : 0;
     }
     before += __shfl_xor(before, 1, kWaveSize);
     before += __shfl_xor(before, 2, kWaveSize);
+    before += __shfl_xor(before, 4, kWaveSize);
     if (part == 0 && t < N) keep[(int64_t)img * N + t] = (uint8_t)((t == 0 || before < k - 1) ? 1 : 0);
 }
 
