@@ -171,29 +171,34 @@ def late_blocks_case(torch, w, label: str, depth: int = 8, tight_cap: bool = Fal
     return rec
 
 
-def late_blocks_in_flight_case(torch, w, label: str, batches: int, keep_prob: float, depth: int = 8):
-    """Several independent batches in flight: one PackedBlocks graph per batch, each replayed on its own
-    HIP stream (default priority).  At a few thousand rows every kernel of the block is bound by latency
-    and leaves most of the chip idle, so kernels of different batches overlap."""
-    hint = int(round(w.B * (1 + (w.N - 1) * keep_prob)))
-    pbs = [PackedBlocks(w, depth, rows_hint=hint) for _ in range(batches)]
+def in_flight(torch, make, batches: int, steps: int = 40):
+    """Wall time per batch with `batches` independent pipelines in flight: one graph per pipeline (make()
+    returns an object with run()), each replayed on its own HIP stream (default priority, chosen by
+    pick_streams), against one pipeline alone."""
     graphs = []
-    for pb in pbs:
-        pb.run()
+    for _ in range(batches):
+        obj = make()
+        obj.run()
         torch.cuda.synchronize()
-        graphs.append(capture(torch, pb.run))
+        graphs.append((capture(torch, obj.run), obj))
 
     def bind(selection):
         def go():
-            for g, st in zip(graphs, selection):
+            for (g, _), st in zip(graphs, selection):
                 with torch.cuda.stream(st):
                     g.replay()
         return go
     _, go = pick_streams(torch, batches, bind, burst=10)
     for _ in range(5):
         go()
-    per_batch = wall_steps(torch, go, 40) / batches
-    one = wall_steps(torch, graphs[0].replay, 40)
+    return wall_steps(torch, go, steps) / batches, wall_steps(torch, graphs[0][0].replay, steps)
+
+
+def late_blocks_in_flight_case(torch, w, label: str, batches: int, keep_prob: float, depth: int = 8):
+    """Several independent batches in flight through the packed blocks.  At a few thousand rows every kernel
+    of the block is bound by latency and leaves most of the chip idle, so kernels of different batches overlap."""
+    hint = int(round(w.B * (1 + (w.N - 1) * keep_prob)))
+    per_batch, one = in_flight(torch, lambda: PackedBlocks(w, depth, rows_hint=hint), batches)
     return {"case": label, "workload": w.name, "B": w.B, "T": w.T, "depth": depth, "batches_in_flight": batches,
             "wall_us_per_batch": per_batch * 1e6, "wall_us_per_batch_alone": one * 1e6,
             "images_per_s_through_late_blocks": w.B / per_batch, "tokens_per_s": w.T * depth / per_batch}
@@ -211,10 +216,12 @@ def progressive_case(torch, B: int, label: str):
         return pb, event_time_us(torch, g.replay, iters=10)[0], wall_steps(torch, g.replay, 20) * 1e6
     pb, gpu_us, wall_us = timed((3, 6, 9))
     _, dense_us, _ = timed(())
+    per_batch, _ = in_flight(torch, lambda: ProgressiveBlocks(B=B, depth=12, prune_at=(3, 6, 9), keep_ratio=0.7), 3, steps=15)
     return {"case": label, "B": B, "N": pb.N, "tokens_per_image": pb.lengths, "kernels_in_graph": pb.launches,
             "graph_gpu_us": gpu_us, "graph_wall_us": wall_us, "unpruned_graph_gpu_us": dense_us,
             "speedup_vs_unpruned": dense_us / gpu_us, "token_blocks": pb.tokens(),
-            "images_per_s": B / (wall_us * 1e-6)}
+            "images_per_s": B / (wall_us * 1e-6), "wall_us_per_batch_3_in_flight": per_batch * 1e6,
+            "images_per_s_3_in_flight": B / per_batch}
 
 
 def mask_producer_case(torch, B: int = 32, N: int = 197, k: int = 40):
