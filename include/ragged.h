@@ -224,7 +224,7 @@ int ragged_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int
  *                           result and the rows written do not depend on it).  0 means rows_cap.
  *   act                     0: none, 1: GELU in its erf form t * Phi(t)
  *
- * Supported: dt = F16 or BF16, N a multiple of 128, K a multiple of 64 and <= 2^22.  MFMA with fp32
+ * Supported: dt = F16 or BF16, N and K multiples of 64, K <= 2^22.  MFMA with fp32
  * accumulation; bias, activation and residual are applied in fp32 before the single rounding to dt.
  */
 int ragged_linear(const void* x, const void* w, const void* bias, const void* residual, void* y,

@@ -456,7 +456,8 @@ hipError_t launch_linear_shape(const void* x, const void* w, const void* bias, c
 //     least half the CUs idle: what limits a small problem is how many bytes the chip has in flight, and
 //     four times as many work-groups, each with two rings, keep more of them going
 //     (1334 x 768 x 3072: 19 against 32; 1334 x 768 x 768: 7.9 against 8.7);
-//   * else 128 x 128 tiles, four wavefronts, two work-groups per CU.
+//   * else 128 x 128 tiles, four wavefronts, two work-groups per CU (N an odd multiple of 64, as in the
+//     192-wide DeiT-Tiny blocks: 64 x 64 tiles whatever the size).
 // Rings of three and four stages were measured too: no gain over two except at 1334 x 768 x 3072, where
 // the 64 x 64 shape is faster still.
 template <typename In>
@@ -467,9 +468,11 @@ hipError_t launch_linear_typed(const void* x, const void* w, const void* bias, c
     const int64_t big_tiles = (int64_t)((rows_hint + 255) / 256) * (N / 256);
     if (N % 256 == 0 && (big_tiles >= kBigTileMinGroups || (ksteps >= 32 && big_tiles >= 128)))
         return launch_linear_shape<In, 4, 2, 8, 2, 1>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
-    const int64_t small_tiles = (int64_t)((rows_hint + 127) / 128) * (N / 128);
-    if (small_tiles <= kSplitMaxGroups && ksteps % 2 == 0)
+    const int64_t small_tiles = (int64_t)((rows_hint + 127) / 128) * ((N + 127) / 128);
+    if ((small_tiles <= kSplitMaxGroups || N % 128 != 0) && ksteps % 2 == 0)
         return launch_linear_shape<In, 1, 1, 4, 2, 2>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
+    if (N % 128 != 0)          // an odd multiple of 64 features and an odd number of k-steps: 64 x 64 tiles, one wavefront
+        return launch_linear_shape<In, 1, 1, 4, 2, 1>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
     return launch_linear_shape<In, 2, 2, 4, 2, 1>(x, w, bias, res, y, rows_cap, rows_dev, N, K, act, stream);
 }
 

@@ -140,8 +140,8 @@ int ragged_linear(const void* x, const void* w, const void* bias, const void* re
     if (!x || !w || !y) return RAGGED_ERR_NULL;
     if (rows_hint < 0 || rows_hint > rows_cap) return RAGGED_ERR_SHAPE;
     if (rows_cap < 1 || rows_cap > (int64_t)INT32_MAX - 256 || N <= 0 || K <= 0 || K > (1 << 22)) return RAGGED_ERR_SHAPE;
-    if (rows_cap * (int64_t)(N / 128 + 1) > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;    // 32-bit grid
-    if (!is16bit(dt) || (N % 128) != 0 || (K % 64) != 0 || (act != 0 && act != 1)) return RAGGED_ERR_UNSUPPORTED;
+    if (rows_cap * (int64_t)(N / 64 + 1) > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;    // 32-bit grid
+    if (!is16bit(dt) || (N % 64) != 0 || (K % 64) != 0 || (act != 0 && act != 1)) return RAGGED_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(residual))
         return RAGGED_ERR_UNSUPPORTED;
     return from_hip(ragged::launch_linear(x, w, bias, residual, y, (int)rows_cap, rows_dev,

@@ -150,7 +150,7 @@ def test_linear_validation(lib):
     for bad in (dict(rows=0), dict(N=0), dict(K=-64), dict(K=(1 << 22) + 64), dict(rows=1 << 31),
                 dict(hint=-1), dict(hint=17)):
         assert call(**bad) == 2
-    for bad in (dict(N=192), dict(K=96), dict(act=2), dict(dt=2), dict(x=FAKE + 2), dict(b=FAKE + 8), dict(r=FAKE + 4)):
+    for bad in (dict(N=160), dict(K=96), dict(act=2), dict(dt=2), dict(x=FAKE + 2), dict(b=FAKE + 8), dict(r=FAKE + 4)):
         assert call(**bad) == 3
 
 

@@ -131,6 +131,14 @@ def test_linear_random_shapes(seed):
                  residual=bool(ri(0, 1)), rows=rows, cap=cap, seed=seed, hint=hint)
 
 
+@pytest.mark.parametrize("M,N,K,act", [(500, 192, 192, "none"), (237, 576, 192, "none"), (1000, 768, 192, "gelu"),
+                                        (300, 192, 768, "none"), (65, 64, 64, "none"), (130, 320, 128, "gelu")])
+def test_linear_feature_counts_that_are_odd_multiples_of_64(M, N, K, act):
+    """Widths of the DeiT-Tiny blocks (C = 192: 192, 576, 768) and other odd multiples of 64."""
+    check_linear(M, N, K, act=act, residual=True, seed=11)
+    check_linear(M, N, K, dtype="bf16", act=act, bias=False, seed=12)
+
+
 def test_linear_residual_in_place_and_gelu_tails():
     tdt = torch.float16
     M, N, K = 200, 256, 128

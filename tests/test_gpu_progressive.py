@@ -75,9 +75,11 @@ def test_run_is_reproducible_and_graph_replays_match_eager():
         assert all(torch.equal(a, b) for a, b in zip(pb.keep, want_keep))
 
 
-def test_deit_b_shape_runs_and_keeps_class_tokens():
-    """Full-width blocks (C = 768) on a small batch: lengths 197 -> 138 -> 97 -> 68, class tokens survive."""
-    pb = ProgressiveBlocks(B=2, depth=12, prune_at=(3, 6, 9), keep_ratio=0.7, seed=5)
+@pytest.mark.parametrize("H", [12, 6, 3])
+def test_deit_shapes_run_and_keep_class_tokens(H):
+    """Blocks of DeiT-Base / Small / Tiny width (C = 768, 384, 192) on a small batch: lengths
+    197 -> 138 -> 97 -> 68, class tokens survive."""
+    pb = ProgressiveBlocks(B=2, H=H, depth=12, prune_at=(3, 6, 9), keep_ratio=0.7, seed=5)
     assert pb.lengths == [197, 138, 97, 68] and pb.launches == 95
     pb.run()
     torch.cuda.synchronize()
