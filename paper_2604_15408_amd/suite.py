@@ -266,9 +266,11 @@ def main():
         emit(cold_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "cold_headline", sets=32))
         emit(cold_case(torch, wl.pipeline()[0], "cold_dense_bs64", sets=6))
     if want("uniform"):
-        emit(case(torch, wl.uniform(32, 40), "uniform_lengths"))        # the paper's BS=32, 40 tok/img row
+        # the paper's kernel-latency table (Section 3): BS 32 and 64 at 0 / 50 / 80 % pruning = 197 / 99 / 40 tokens per image
+        for B in (32, 64):
+            for per_image in (197, 99, 40):
+                emit(case(torch, wl.uniform(B, per_image), "uniform_lengths"))
         emit(case(torch, wl.uniform(1, 40), "uniform_lengths"))
-        emit(case(torch, wl.uniform(32, 197), "uniform_lengths"))
     if want("mask_producer"):
         emit(mask_producer_case(torch))
     if want("sweep"):
