@@ -224,6 +224,26 @@ def progressive_case(torch, B: int, label: str):
             "images_per_s_3_in_flight": B / per_batch}
 
 
+def prune_once_case(torch, B: int, H: int, label: str):
+    """The paper's Section 4.3 schedule on a 12-block encoder of DeiT width H*64 with synthetic weights: four
+    blocks on all tokens, one pruning stage (top-k l2 score) in front of block 4, eight blocks on the packed
+    rows, class tokens read from the packed buffer -- for several keep ratios, one HIP graph each."""
+    out = {"case": label, "B": B, "C": H * 64, "N": 197, "graph_gpu_us": {}, "images_per_s": {}, "tokens_after_pruning": {}}
+    for ratio in (1.0, 0.5, 0.2, 0.1):
+        pb = ProgressiveBlocks(B=B, H=H, depth=12, prune_at=() if ratio == 1.0 else (4,), keep_ratio=ratio)
+        pb.run()
+        torch.cuda.synchronize()
+        g = capture(torch, pb.run)
+        us = event_time_us(torch, g.replay, iters=10)[0]
+        key = f"keep_{ratio}"
+        out["graph_gpu_us"][key] = us
+        out["images_per_s"][key] = B / (us * 1e-6)
+        out["tokens_after_pruning"][key] = pb.lengths[-1]
+    base = out["graph_gpu_us"]["keep_1.0"]
+    out["speedup_vs_unpruned"] = {k: base / v for k, v in out["graph_gpu_us"].items()}
+    return out
+
+
 def mask_producer_case(torch, B: int = 32, N: int = 197, k: int = 40):
     """The keep-mask producer in front of pack: fp64 l2 scores + per-image top-k, then pack."""
     from . import binding
@@ -297,6 +317,11 @@ def main():
         emit(late_blocks_case(torch, wl.uniform(32, 40), "late_blocks_uniform40_tight_cap", tight_cap=True))
         emit(late_blocks_case(torch, wl.deit_b_pruned(0.5, 8, "f16", 1005), "late_blocks_bs8_keep0.5", keep_prob=0.5))
         emit(late_blocks_case(torch, wl.deit_b_pruned(1.0, 64, "f16", 1006), "late_blocks_bs64_dense"))
+    if want("prune_once"):
+        for H, name in ((12, "base"), (6, "small"), (3, "tiny")):
+            emit(prune_once_case(torch, 32, H, f"prune_once_deit_{name}_bs32"))
+        emit(prune_once_case(torch, 8, 12, "prune_once_deit_base_bs8"))
+        emit(prune_once_case(torch, 128, 12, "prune_once_deit_base_bs128"))
     if want("progressive"):
         emit(progressive_case(torch, 32, "progressive_12_blocks_bs32"))
         emit(progressive_case(torch, 8, "progressive_12_blocks_bs8"))
