@@ -244,6 +244,36 @@ def prune_once_case(torch, B: int, H: int, label: str):
     return out
 
 
+LINEAR_LAYERS = (("qkv", 2304, 768, "none"), ("out", 768, 768, "none"), ("fc1", 3072, 768, "gelu"), ("fc2", 768, 3072, "none"))
+
+
+def linear_case(torch, rows: int, shape=None, library: bool = True):
+    """ragged_linear alone on the four layer shapes of a DeiT-B block at `rows` rows (bias; GELU on fc1): us per
+    launch in a graph of 10 and TFLOP/s; for context the framework library's GEMM (torch.addmm, no GELU) on
+    the same shape.  shape = (N, K) restricts the run to one layer shape (used under the profiler)."""
+    from . import binding
+    dev = "cuda:0"
+    rec = {"case": "linear_layers", "rows": rows, "us": {}, "tflops": {}, "library_addmm_us": {}}
+    layers = [("custom", shape[0], shape[1], "none")] if shape else LINEAR_LAYERS
+    for name, N, K, act in layers:
+        g = torch.Generator(device=dev).manual_seed(rows + N)
+        x = torch.randn(rows, K, generator=g, device=dev).half()
+        w = (torch.randn(N, K, generator=g, device=dev) * K ** -0.5).half()
+        b = torch.randn(N, generator=g, device=dev).half()
+        y = torch.zeros(rows, N, device=dev).half()
+        fn = lambda: binding.ragged_linear(x, w, b, None, y, None, act)
+        us = event_time_us(torch, capture(torch, fn, 10).replay, iters=20)[0] / 10
+        rec["us"][name], rec["tflops"][name] = us, 2 * rows * N * K / us / 1e6
+        if library:
+            wt = w.t().contiguous()
+            lib = lambda: torch.addmm(b, x, wt, out=y)
+            for _ in range(3):
+                lib()
+            torch.cuda.synchronize()
+            rec["library_addmm_us"][name] = event_time_us(torch, capture(torch, lib, 10).replay, iters=20)[0] / 10
+    return rec
+
+
 def mask_producer_case(torch, B: int = 32, N: int = 197, k: int = 40):
     """The keep-mask producer in front of pack: fp64 l2 scores + per-image top-k, then pack."""
     from . import binding
@@ -265,6 +295,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default=None)
     ap.add_argument("--only", default=None, help="run only the cases whose name starts with this (e.g. late_blocks)")
+    ap.add_argument("--linear-shape", default=None, metavar="ROWS,N,K",
+                    help="with --only linear: one ragged_linear shape only, without the library GEMM (for the profiler)")
     args = ap.parse_args()
     import torch
     from . import binding
@@ -317,6 +349,13 @@ def main():
         emit(late_blocks_case(torch, wl.uniform(32, 40), "late_blocks_uniform40_tight_cap", tight_cap=True))
         emit(late_blocks_case(torch, wl.deit_b_pruned(0.5, 8, "f16", 1005), "late_blocks_bs8_keep0.5", keep_prob=0.5))
         emit(late_blocks_case(torch, wl.deit_b_pruned(1.0, 64, "f16", 1006), "late_blocks_bs64_dense"))
+    if want("linear"):
+        if args.linear_shape:
+            rows, N, K = (int(v) for v in args.linear_shape.split(","))
+            emit(linear_case(torch, rows, (N, K), library=False))
+        else:
+            for rows in (12608, 6304, 1334):
+                emit(linear_case(torch, rows))
     if want("prune_once"):
         for H, name in ((12, "base"), (6, "small"), (3, "tiny")):
             emit(prune_once_case(torch, 32, H, f"prune_once_deit_{name}_bs32"))
