@@ -104,6 +104,23 @@ def test_small_heads_and_odd_sizes():
     check(wl.Workload("long", 3, 1000, 3, 64, "f16", 34, keep), 1)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches(seed):
+    """Seeded random geometry, keep probability, dtype and fill mode, with images that keep nothing and
+    batches whose class tokens are not forced."""
+    g = torch.Generator().manual_seed(7000 + seed)
+    ri = lambda lo, hi: int(torch.randint(lo, hi + 1, (1,), generator=g))
+    B, N, H = ri(1, 12), ri(1, 400), ri(1, 6)
+    p = [0.0, 0.05, 0.2, 0.5, 0.9, 1.0][ri(0, 5)]
+    keep = (torch.rand(B, N, generator=g) < p).to(torch.uint8)
+    if ri(0, 1):
+        keep[:, 0] = 1
+    if ri(0, 3) == 0:
+        keep[ri(0, B - 1)] = 0
+    check(wl.Workload(f"random{seed}", B, N, H, 64, "f16", 500 + seed, keep), ri(0, 1),
+          [torch.float16, torch.bfloat16][ri(0, 1)])
+
+
 def test_graph_replays_match_eager():
     from paper_2604_15408_amd.harness import capture
     w = wl.deit_b_pruned(0.3, 8)
