@@ -108,31 +108,35 @@ def _check(fn: str, status: int) -> None:
         raise RaggedError(fn, status)
 
 
+def _pack_args(x, keep, packed, cu_seqlens, gather_idx, stream):
+    B, N, C = x.shape
+    cap = packed.shape[0]
+    return (_dev(x, "x", (torch.float16, torch.bfloat16)),
+            _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)), B, N, C, _DTYPE_CODE[x.dtype],
+            _dev(packed, "packed", x.dtype, (cap, C)), cap,
+            _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
+            _dev(gather_idx, "gather_idx", torch.int32, (cap,)), _stream(stream))
+
+
 def ragged_pack(x, keep, packed, cu_seqlens, gather_idx, stream=None) -> None:
     """x [B,N,C] f16/bf16, keep [B,N] uint8/bool -> packed [cap,C], cu_seqlens [B+1] i32,
     gather_idx [cap] i32 (all caller-allocated; cap = packed.shape[0])."""
-    B, N, C = x.shape
-    cap = packed.shape[0]
-    st = load().ragged_pack(
-        _dev(x, "x", (torch.float16, torch.bfloat16)),
-        _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)), B, N, C, _DTYPE_CODE[x.dtype],
-        _dev(packed, "packed", x.dtype, (cap, C)), cap,
-        _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
-        _dev(gather_idx, "gather_idx", torch.int32, (cap,)), _stream(stream))
-    _check("ragged_pack", st)
+    _check("ragged_pack", load().ragged_pack(*_pack_args(x, keep, packed, cu_seqlens, gather_idx, stream)))
+
+
+def _attn_args(q, k, v, o, cu_seqlens, max_seqlen, scale, stream):
+    rows, H, D = q.shape
+    B = cu_seqlens.shape[0] - 1
+    return (_dev(q, "q", (torch.float16, torch.bfloat16)), _dev(k, "k", q.dtype, q.shape),
+            _dev(v, "v", q.dtype, q.shape), _dev(o, "o", (q.dtype, torch.float32), q.shape),
+            _dev(cu_seqlens, "cu_seqlens", torch.int32), B, int(max_seqlen), H, D, float(scale),
+            _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], _stream(stream))
 
 
 def ragged_attn(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=None) -> None:
     """q,k,v [rows,H,D] f16/bf16 and o [rows,H,D] (same dtype or f32); only rows < cu_seqlens[-1]
     are read / written."""
-    rows, H, D = q.shape
-    B = cu_seqlens.shape[0] - 1
-    st = load().ragged_attn(
-        _dev(q, "q", (torch.float16, torch.bfloat16)), _dev(k, "k", q.dtype, q.shape),
-        _dev(v, "v", q.dtype, q.shape), _dev(o, "o", (q.dtype, torch.float32), q.shape),
-        _dev(cu_seqlens, "cu_seqlens", torch.int32), B, int(max_seqlen), H, D, float(scale),
-        _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], _stream(stream))
-    _check("ragged_attn", st)
+    _check("ragged_attn", load().ragged_attn(*_attn_args(q, k, v, o, cu_seqlens, max_seqlen, scale, stream)))
 
 
 def _token_rows(t: torch.Tensor, name: str, dtype, shape):
@@ -308,18 +312,20 @@ def ragged_keep_topk(scores, k: int, keep, stream=None) -> None:
         _stream(stream)))
 
 
+def _unpack_args(src, keep, cu_seqlens, gather_idx, out, fill_mode, stream):
+    B, N, C = out.shape
+    return (_dev(src, "src", (torch.float16, torch.bfloat16)),
+            None if keep is None else _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)),
+            _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
+            None if gather_idx is None else _dev(gather_idx, "gather_idx", torch.int32),
+            B, N, C, _DTYPE_CODE[src.dtype], _dev(out, "out", src.dtype), int(fill_mode), _stream(stream))
+
+
 def ragged_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> None:
     """src [rows,C] -> out [B,N,C].  fill_mode 0 needs gather_idx (keep may be None); fill_mode 1
     needs keep (gather_idx may be None)."""
-    B, N, C = out.shape
-    st = load().ragged_unpack(
-        _dev(src, "src", (torch.float16, torch.bfloat16)),
-        None if keep is None else _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)),
-        _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
-        None if gather_idx is None else _dev(gather_idx, "gather_idx", torch.int32),
-        B, N, C, _DTYPE_CODE[src.dtype], _dev(out, "out", src.dtype), int(fill_mode),
-        _stream(stream))
-    _check("ragged_unpack", st)
+    _check("ragged_unpack",
+           load().ragged_unpack(*_unpack_args(src, keep, cu_seqlens, gather_idx, out, fill_mode, stream)))
 
 
 _UNTYPED = None
@@ -358,24 +364,13 @@ class Prepared:
 
 
 def prepare_pack(x, keep, packed, cu_seqlens, gather_idx, stream=None) -> Prepared:
-    B, N, C = x.shape
-    cap = packed.shape[0]
-    args = (_dev(x, "x", (torch.float16, torch.bfloat16)),
-            _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)), B, N, C, _DTYPE_CODE[x.dtype],
-            _dev(packed, "packed", x.dtype, (cap, C)), cap,
-            _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
-            _dev(gather_idx, "gather_idx", torch.int32, (cap,)), _stream(stream))
-    return Prepared("ragged_pack", load().ragged_pack, args, (x, keep, packed, cu_seqlens, gather_idx))
+    return Prepared("ragged_pack", load().ragged_pack, _pack_args(x, keep, packed, cu_seqlens, gather_idx, stream),
+                    (x, keep, packed, cu_seqlens, gather_idx))
 
 
 def prepare_attn(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=None) -> Prepared:
-    rows, H, D = q.shape
-    B = cu_seqlens.shape[0] - 1
-    args = (_dev(q, "q", (torch.float16, torch.bfloat16)), _dev(k, "k", q.dtype, q.shape),
-            _dev(v, "v", q.dtype, q.shape), _dev(o, "o", (q.dtype, torch.float32), q.shape),
-            _dev(cu_seqlens, "cu_seqlens", torch.int32), B, int(max_seqlen), H, D, float(scale),
-            _DTYPE_CODE[q.dtype], _DTYPE_CODE[o.dtype], _stream(stream))
-    return Prepared("ragged_attn", load().ragged_attn, args, (q, k, v, o, cu_seqlens))
+    return Prepared("ragged_attn", load().ragged_attn, _attn_args(q, k, v, o, cu_seqlens, max_seqlen, scale, stream),
+                    (q, k, v, o, cu_seqlens))
 
 
 def prepare_attn_strided(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, stream=None) -> Prepared:
@@ -400,14 +395,9 @@ def prepare_attn_padded(q, k, v, o, keep, scale: float, fill_mode: int = 0, stre
 
 
 def prepare_unpack(src, keep, cu_seqlens, gather_idx, out, fill_mode: int, stream=None) -> Prepared:
-    B, N, C = out.shape
-    args = (_dev(src, "src", (torch.float16, torch.bfloat16)),
-            None if keep is None else _dev(keep, "keep", (torch.uint8, torch.bool), (B, N)),
-            _dev(cu_seqlens, "cu_seqlens", torch.int32, (B + 1,)),
-            None if gather_idx is None else _dev(gather_idx, "gather_idx", torch.int32),
-            B, N, C, _DTYPE_CODE[src.dtype], _dev(out, "out", src.dtype), int(fill_mode),
-            _stream(stream))
-    return Prepared("ragged_unpack", load().ragged_unpack, args, (src, keep, cu_seqlens, gather_idx, out))
+    return Prepared("ragged_unpack", load().ragged_unpack,
+                    _unpack_args(src, keep, cu_seqlens, gather_idx, out, fill_mode, stream),
+                    (src, keep, cu_seqlens, gather_idx, out))
 
 
 def ragged_noop(grid: int, stream=None) -> None:

@@ -63,6 +63,7 @@ def build(verbose: bool = False, extra_flags=()) -> Path:
         raise RuntimeError(f"link failed:\n{res.stderr}")
     os.replace(tmp, LIB)
     build_call_cost(hipcc)
+    build_ceilings(hipcc)
     return LIB
 
 
@@ -77,6 +78,21 @@ def build_call_cost(hipcc: str) -> Path:
     if res.returncode != 0:
         raise RuntimeError(f"building ragged_call_cost failed:\n{res.stderr}")
     return CALL_COST
+
+
+CEILINGS = PKG / "libragged_ceilings.so"
+
+
+def build_ceilings(hipcc: str) -> Path:
+    """The benchmark's own ceiling kernels (native/ceilings.hip: streaming read / copy, MFMA loop); not part
+    of the C ABI, so they live in a shared library of their own."""
+    tmp = CEILINGS.with_suffix(f".tmp{os.getpid()}.so")
+    res = subprocess.run([hipcc, *HIPCC_FLAGS, "-shared", "-o", str(tmp), str(PKG / "native" / "ceilings.hip")],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"building libragged_ceilings.so failed:\n{res.stderr}")
+    os.replace(tmp, CEILINGS)
+    return CEILINGS
 
 
 if __name__ == "__main__":

@@ -511,13 +511,13 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
     const int pairs8 = (pairs + kXcds - 1) / kXcds * kXcds;
     const int group = pairs8 < kGroup ? pairs8 : kGroup;
     const int batches = (pairs + group - 1) / group;
-    hipLaunchKernelGGL((attn_kernel<In, OutT, MODE>), dim3(batches * q_tiles * group),
-                       dim3(kAttnThreads), 0, stream,
+    const hipError_t err = launch_kernel((attn_kernel<In, OutT, MODE>), dim3(batches * q_tiles * group),
+                       dim3(kAttnThreads), stream,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                        static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, keep, n_tok,
                        fill_mode, H, in_tok, out_tok, pairs, q_tiles, group, fabsf(scale) * kLog2e,
                        scale < 0.f ? 1 : 0, step);
-    return hipGetLastError();
+    return err;
 }
 
 template <int MODE>

@@ -13,6 +13,18 @@ constexpr int kWaveSize = 64;          // CDNA wavefront width
 constexpr int kBlockThreads = 256;     // 4 wavefronts per work-group in every kernel here
 constexpr int kXcds = 8;               // MI355X: 8 accelerator dies, work-groups dealt round-robin
 
+// Enqueue one kernel and return the status of THIS launch.  (hipLaunchKernelGGL followed by
+// hipGetLastError would also report -- and clear -- an error that unrelated earlier calls of the
+// caller left behind.)  The arguments are converted to the kernel's parameter types.
+template <typename T>
+struct kernel_param { typedef T type; };
+template <typename... Params>
+inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
+                                typename kernel_param<Params>::type... args) {
+    void* ptrs[sizeof...(Params) > 0 ? sizeof...(Params) : 1] = {const_cast<void*>(static_cast<const void*>(&args))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, stream);
+}
+
 // Host launchers (one kernel each).  All arguments have been validated by the C ABI layer.
 hipError_t launch_pack(const void* x, const uint8_t* keep, int B, int N, int C, void* packed,
                        int64_t cap_rows, int32_t* cu_seqlens, int32_t* gather_idx,

@@ -99,8 +99,8 @@ __device__ __forceinline__ void pack16(BF16, const float (&v)[16], uint4& a, uin
 template <typename In, int ACT, bool HAS_RES, int WNW, int WMW, int MT, int STAGES, int KSPLIT>
 __global__ __launch_bounds__(kWaveSize * WNW * WMW * KSPLIT, (WNW * WMW * KSPLIT >= 8) ? 1 : 8 / (WNW * WMW * KSPLIT))
 void linear_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
-                   const uint16_t* __restrict__ bias, const uint16_t* __restrict__ res,
-                   uint16_t* __restrict__ y, int rows_cap, const int32_t* __restrict__ rows_dev, int N, int K,
+                   const uint16_t* __restrict__ bias, const uint16_t* res,   // res may alias y: no restrict
+                   uint16_t* y, int rows_cap, const int32_t* __restrict__ rows_dev, int N, int K,
                    int n_tiles) {
     typedef typename In::vec8 vec8;
     constexpr int WAVES = WNW * WMW;
@@ -359,8 +359,8 @@ constexpr int kLnChunks = 4;                                   // 16-byte chunks
 
 template <typename In>
 __global__ __launch_bounds__(kBlockThreads)
-void layernorm_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ gamma,
-                      const uint16_t* __restrict__ beta, uint16_t* __restrict__ y, int rows_cap,
+void layernorm_kernel(const uint16_t* x, const uint16_t* __restrict__ gamma,          // y may be x: no restrict
+                      const uint16_t* __restrict__ beta, uint16_t* y, int rows_cap,
                       const int32_t* __restrict__ rows_dev, int C, float eps) {
     int rows = rows_cap;
     if (rows_dev) { const int r = *rows_dev; rows = r < rows ? r : rows; }
@@ -436,15 +436,16 @@ hipError_t launch_linear_shape(const void* x, const void* w, const void* bias, c
     const uint16_t* bp = static_cast<const uint16_t*>(bias);
     const uint16_t* rp = static_cast<const uint16_t*>(res);
     uint16_t* yp = static_cast<uint16_t*>(y);
+    hipError_t err;
     if (act == 1 && res)
-        hipLaunchKernelGGL((linear_kernel<In, 1, true, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        err = launch_kernel((linear_kernel<In, 1, true, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else if (act == 1)
-        hipLaunchKernelGGL((linear_kernel<In, 1, false, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        err = launch_kernel((linear_kernel<In, 1, false, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else if (res)
-        hipLaunchKernelGGL((linear_kernel<In, 0, true, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+        err = launch_kernel((linear_kernel<In, 0, true, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
     else
-        hipLaunchKernelGGL((linear_kernel<In, 0, false, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, 0, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
-    return hipGetLastError();
+        err = launch_kernel((linear_kernel<In, 0, false, WNW, WMW, MT, STAGES, KSPLIT>), grid, block, stream, xp, wp, bp, rp, yp, rows_cap, rows_dev, N, K, n_tiles);
+    return err;
 }
 
 // Shape choice from what the host knows (the expected row count -- the capacity unless the caller
@@ -496,11 +497,12 @@ hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, 
     const uint16_t* gp = static_cast<const uint16_t*>(gamma);
     const uint16_t* bp = static_cast<const uint16_t*>(beta);
     uint16_t* yp = static_cast<uint16_t*>(y);
+    hipError_t err;
     if (dt == RAGGED_F16)
-        hipLaunchKernelGGL((layernorm_kernel<F16>), grid, block, 0, stream, xp, gp, bp, yp, rows_cap, rows_dev, C, eps);
+        err = launch_kernel((layernorm_kernel<F16>), grid, block, stream, xp, gp, bp, yp, rows_cap, rows_dev, C, eps);
     else
-        hipLaunchKernelGGL((layernorm_kernel<BF16>), grid, block, 0, stream, xp, gp, bp, yp, rows_cap, rows_dev, C, eps);
-    return hipGetLastError();
+        err = launch_kernel((layernorm_kernel<BF16>), grid, block, stream, xp, gp, bp, yp, rows_cap, rows_dev, C, eps);
+    return err;
 }
 
 }  // namespace ragged

@@ -72,17 +72,18 @@ hipError_t launch_token_scores_l2(const void* x, int64_t rows, int C, ragged_dty
                                   hipStream_t stream) {
     const int per = kBlockThreads / kWaveSize;
     const dim3 grid((unsigned)((rows + per - 1) / per)), block(kBlockThreads);
+    hipError_t err;
     if (dt == RAGGED_F16)
-        hipLaunchKernelGGL((token_scores_l2_kernel<f16x8>), grid, block, 0, stream, static_cast<const uint4*>(x), rows, C / 8, scores);
+        err = launch_kernel((token_scores_l2_kernel<f16x8>), grid, block, stream, static_cast<const uint4*>(x), rows, C / 8, scores);
     else
-        hipLaunchKernelGGL((token_scores_l2_kernel<bf16x8>), grid, block, 0, stream, static_cast<const uint4*>(x), rows, C / 8, scores);
-    return hipGetLastError();
+        err = launch_kernel((token_scores_l2_kernel<bf16x8>), grid, block, stream, static_cast<const uint4*>(x), rows, C / 8, scores);
+    return err;
 }
 
 hipError_t launch_keep_topk(const double* scores, int B, int N, int k, uint8_t* keep, hipStream_t stream) {
     const int chunks = (N + kTopkTokens - 1) / kTopkTokens;
-    hipLaunchKernelGGL(keep_topk_kernel, dim3(B * chunks), dim3(kBlockThreads), 0, stream, scores, N, k, chunks, keep);
-    return hipGetLastError();
+    const hipError_t err = launch_kernel(keep_topk_kernel, dim3(B * chunks), dim3(kBlockThreads), stream, scores, N, k, chunks, keep);
+    return err;
 }
 
 }  // namespace ragged

@@ -48,10 +48,16 @@ __device__ __forceinline__ short4v lds_read_tr(uint32_t addr) {
 // One wavefront instruction of the global->LDS load: lane i fetches the 16 bytes at base + voff and
 // the hardware stores them at LDS address lds_dst + 16*i.  The compiler is not told about the LDS
 // write; callers order it against LDS reads with wait_vm<>() and a barrier.
+// M0 (the LDS destination register of this instruction) is written inside the asm and listed as clobbered,
+// so the compiler never keeps a value of its own there across the statement; clang remarks that M0 is a
+// reserved register whenever it appears in a clobber list, which is expected here.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(uint32_t lds_dst, uint32_t voff, const void* base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_dst), "v"(voff), "s"(base) : "memory");
+                 :: "s"(lds_dst), "v"(voff), "s"(base) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 template <int N>
 __device__ __forceinline__ void wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");

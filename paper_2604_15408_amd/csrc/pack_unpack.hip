@@ -241,29 +241,30 @@ hipError_t launch_pack(const void* x, const uint8_t* keep, int B, int N, int C, 
     // the early-load variant keeps the first 16 KB of mask prefix in registers; beyond that the
     // remaining prefix loads would queue behind the row loads, so larger masks take the plain order
     const bool early = chunk <= 4 * kMaxEarly && C / 8 <= 2 * kWaveSize && (int64_t)B * N <= 16384;
-    hipLaunchKernelGGL(early ? pack_kernel<true> : pack_kernel<false>, dim3(B * cpi),
-                       dim3(kBlockThreads), 0, stream, static_cast<const uint4*>(x), keep, N, C / 8,
+    const hipError_t err = launch_kernel(early ? pack_kernel<true> : pack_kernel<false>, dim3(B * cpi),
+                       dim3(kBlockThreads), stream, static_cast<const uint4*>(x), keep, N, C / 8,
                        static_cast<uint4*>(packed), cap_rows, cu_seqlens, gather_idx, chunk, cpi);
-    return hipGetLastError();
+    return err;
 }
 
 hipError_t launch_unpack(const void* src, const uint8_t* keep, const int32_t* cu_seqlens,
                          const int32_t* gather_idx, int B, int N, int C, void* out, int fill_mode,
                          hipStream_t stream) {
+    hipError_t err;
     if (fill_mode == 0) {
         const int64_t rows = (int64_t)B * N;
         const int grid = (int)((rows + kUnpackRows - 1) / kUnpackRows);
-        hipLaunchKernelGGL(unpack_scatter_kernel, dim3(grid), dim3(kBlockThreads), 0, stream,
+        err = launch_kernel(unpack_scatter_kernel, dim3(grid), dim3(kBlockThreads), stream,
                            static_cast<const uint4*>(src), cu_seqlens, gather_idx, B, C / 8,
                            static_cast<uint4*>(out));
     } else {
         const int chunk = pick_chunk(B, N);
         const int cpi = (N + chunk - 1) / chunk;
-        hipLaunchKernelGGL(unpack_fill_kernel, dim3(B * cpi), dim3(kBlockThreads), 0, stream,
+        err = launch_kernel(unpack_fill_kernel, dim3(B * cpi), dim3(kBlockThreads), stream,
                            static_cast<const uint4*>(src), keep, cu_seqlens, N, C / 8,
                            static_cast<uint4*>(out), chunk, cpi);
     }
-    return hipGetLastError();
+    return err;
 }
 
 hipError_t launch_repack(const void* packed_in, const uint8_t* keep_rows, const int32_t* cu_in, int B,
@@ -272,23 +273,23 @@ hipError_t launch_repack(const void* packed_in, const uint8_t* keep_rows, const 
     int chunk = 8;
     while (chunk < 64 && cap_in / chunk > 4096) chunk *= 2;
     const int grid = (int)(cap_in / chunk) + 1;                // covers every chunk start <= cap_in
-    hipLaunchKernelGGL(repack_kernel, dim3(grid), dim3(kBlockThreads), 0, stream,
+    const hipError_t err = launch_kernel(repack_kernel, dim3(grid), dim3(kBlockThreads), stream,
                        static_cast<const uint4*>(packed_in), keep_rows, cu_in, B, cap_in, C / 8,
                        static_cast<uint4*>(packed_out), cap_out, cu_out, gather_out, chunk);
-    return hipGetLastError();
+    return err;
 }
 
 hipError_t launch_cls_extract(const void* packed, const int32_t* cu_seqlens, int B, int C, void* out,
                               hipStream_t stream) {
     const int per = kBlockThreads / kWaveSize;
-    hipLaunchKernelGGL(cls_extract_kernel, dim3((B + per - 1) / per), dim3(kBlockThreads), 0, stream,
+    const hipError_t err = launch_kernel(cls_extract_kernel, dim3((B + per - 1) / per), dim3(kBlockThreads), stream,
                        static_cast<const uint4*>(packed), cu_seqlens, B, C / 8, static_cast<uint4*>(out));
-    return hipGetLastError();
+    return err;
 }
 
 hipError_t launch_noop(int grid, hipStream_t stream) {
-    hipLaunchKernelGGL(noop_kernel, dim3(grid), dim3(kBlockThreads), 0, stream);
-    return hipGetLastError();
+    const hipError_t err = launch_kernel(noop_kernel, dim3(grid), dim3(kBlockThreads), stream);
+    return err;
 }
 
 }  // namespace ragged

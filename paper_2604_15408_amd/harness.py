@@ -7,6 +7,53 @@ import statistics
 import time
 
 REPLICAS = 20                    # copies of one kernel inside a graph when timing that kernel alone
+BLOCKS = 31                      # timed blocks per measurement: median, p10 and p90 are taken over these
+MIN_BLOCK_STEPS = 1000           # a block lasts at least this many steps (several ms at ViT sizes)
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MFMA_F16_PEAK_TFLOPS = 2500.0    # dense fp16/bf16 MFMA, published
+
+
+def spread(samples):
+    """median, 10th / 90th percentile and mean of a list of samples."""
+    xs = sorted(samples)
+    n = len(xs)
+    pick = lambda f: xs[min(n - 1, max(0, int(round(f * (n - 1)))))]
+    return {"median": statistics.median(xs), "p10": pick(0.10), "p90": pick(0.90), "mean": statistics.fmean(xs)}
+
+
+def block_steps(steps: int) -> int:
+    """Steps per timed block: the smallest multiple of `steps` that reaches MIN_BLOCK_STEPS."""
+    steps = max(1, int(steps))
+    return steps * -(-MIN_BLOCK_STEPS // steps)
+
+
+def wall_blocks(torch, fn, steps: int, blocks: int = BLOCKS):
+    """Wall-clock seconds per step of fn(): `blocks` blocks of block_steps(steps) back-to-back calls, each
+    block bracketed by a device synchronisation; returns spread() over the per-block averages."""
+    n = block_steps(steps)
+    return spread([wall_steps(torch, fn, n) for _ in range(blocks)])
+
+
+def timed_blocks(torch, fn, steps: int, blocks: int = BLOCKS):
+    """wall_blocks() with a pair of HIP events recorded on the launching stream around the calls of every
+    block as well: returns (wall seconds per step, GPU microseconds per step between the two events), both as
+    spread() over the blocks.  The event time is the average duration of one launch inside the timed region,
+    including whatever gap the stream leaves between consecutive kernels."""
+    n = block_steps(steps)
+    wall, gpu = [], []
+    for _ in range(blocks):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall.append((time.perf_counter() - t0) / n)
+        gpu.append(e0.elapsed_time(e1) * 1e3 / n)
+    return spread(wall), spread(gpu)
 
 
 def make_workload(name: str):
@@ -88,23 +135,27 @@ class Path:
                 call()
         return step
 
-    # algorithmic bytes / flops of one launch of each stage (what the method itself must move)
     def algorithmic(self):
-        w, T = self.w, self.T
-        row = w.C * 2
-        sq = sum(n * n for n in w.lengths)
-        unpack_bytes = 2 * T * row + 4 * T if self.fill_mode == 0 else T * row + w.B * w.N * row + w.B * w.N
-        stages = {
-            "pack": {"bytes": w.B * w.N + 2 * T * row + 4 * (w.B + 1) + 4 * T},
-            "attn": {"bytes": 4 * T * row, "flops": 4 * w.D * w.H * sq},
-            "unpack": {"bytes": unpack_bytes},
-        }
-        # the single-launch step moves what the three stages move, except that the attention output
-        # goes straight to both destinations (o is not read back) and gather_idx is not re-read
-        fused = (w.B * w.N + 2 * T * row + 4 * (w.B + 1) + 4 * T) + 4 * T * row + \
-                (T * row if self.fill_mode == 0 else w.B * w.N * row)
-        stages["pack_attn_unpack"] = {"bytes": fused, "flops": stages["attn"]["flops"]}
-        return stages
+        return algorithmic(self.w, self.fill_mode)
+
+
+def algorithmic(w, fill_mode: int = 0):
+    """Algorithmic bytes / flops of one launch of each stage (what the method itself must move)."""
+    T = w.T
+    row = w.C * 2
+    sq = sum(n * n for n in w.lengths)
+    unpack_bytes = 2 * T * row + 4 * T if fill_mode == 0 else T * row + w.B * w.N * row + w.B * w.N
+    stages = {
+        "pack": {"bytes": w.B * w.N + 2 * T * row + 4 * (w.B + 1) + 4 * T},
+        "attn": {"bytes": 4 * T * row, "flops": 4 * w.D * w.H * sq},
+        "unpack": {"bytes": unpack_bytes},
+    }
+    # the single-launch step moves what the three stages move, except that the attention output
+    # goes straight to both destinations (o is not read back) and gather_idx is not re-read
+    fused = (w.B * w.N + 2 * T * row + 4 * (w.B + 1) + 4 * T) + 4 * T * row + \
+            (T * row if fill_mode == 0 else w.B * w.N * row)
+    stages["pack_attn_unpack"] = {"bytes": fused, "flops": stages["attn"]["flops"]}
+    return stages
 
 
 def capture(torch, fn, reps: int = 1):
@@ -123,8 +174,8 @@ def capture(torch, fn, reps: int = 1):
     return g
 
 
-def event_time_us(torch, launch, iters: int, warmup: int = 5):
-    """Median / mean GPU time of launch() in microseconds, HIP events on the launching stream."""
+def event_samples_us(torch, launch, iters: int, warmup: int = 5):
+    """GPU time of launch() in microseconds, one sample per call, HIP events on the launching stream."""
     for _ in range(warmup):
         launch()
     torch.cuda.synchronize()
@@ -137,7 +188,20 @@ def event_time_us(torch, launch, iters: int, warmup: int = 5):
         e1.record()
         e1.synchronize()
         samples.append(e0.elapsed_time(e1) * 1e3)
+    return samples
+
+
+def event_time_us(torch, launch, iters: int, warmup: int = 5):
+    """Median / mean GPU time of launch() in microseconds."""
+    samples = event_samples_us(torch, launch, iters, warmup)
     return statistics.median(samples), statistics.fmean(samples)
+
+
+def kernel_time_us(torch, fn, iters: int = 50, reps: int = REPLICAS):
+    """One kernel alone: `reps` back-to-back copies of fn() in one HIP graph, HIP events around each of `iters`
+    replays; spread() of the per-copy times in microseconds (includes the in-graph kernel-to-kernel gap)."""
+    g = capture(torch, fn, reps)
+    return spread([t / reps for t in event_samples_us(torch, g.replay, iters)])
 
 
 def pick_streams(torch, n: int, bind, extra: int = 3, burst: int = 300):
@@ -473,3 +537,114 @@ class ProgressiveBlocks:
                 s += 1
             total += self.B * self.lengths[s]
         return total
+
+
+class Ceilings:
+    """What this GPU actually reaches on the two resources the rooflines are drawn against: a streaming read
+    and a streaming copy of 1 GiB (HBM) and a register-resident fp16 MFMA loop (matrix cores).  The kernels
+    live in the benchmark's own shared library (native/ceilings.hip), not in the C ABI."""
+
+    def __init__(self):
+        import ctypes
+        from pathlib import Path as FsPath
+        path = FsPath(__file__).resolve().parent / "libragged_ceilings.so"
+        if not path.exists():
+            raise FileNotFoundError(f"{path} is missing: build it with `python -m paper_2604_15408_amd.build`")
+        lib = ctypes.CDLL(str(path))
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        lib.ceiling_stream_read.argtypes = [vp, i64, vp, i32, i32, vp]
+        lib.ceiling_stream_copy.argtypes = [vp, vp, i64, i32, i32, vp]
+        lib.ceiling_mfma_loop.argtypes = [i32, i32, vp, vp]
+        lib.ceiling_mfma_flops.argtypes = [i32, i32]
+        lib.ceiling_mfma_flops.restype = i64
+        self.lib = lib
+
+    def measure(self, torch, gib: float = 1.0, iters: int = 8):
+        """Best rate over a few launch shapes (1, 2, 4 and 8 work-groups per CU; plain and non-temporal
+        accesses): the rates differ by 20-30 % between shapes on this part, and a ceiling is the best of them."""
+        lib = self.lib
+        words = int(gib * (1 << 30)) // 4
+        src = torch.full((words,), 0x01010101, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        sink = torch.zeros(1024, dtype=torch.int32, device="cuda:0")
+        nbytes = words * 4
+        stream = lambda: torch.cuda.current_stream().cuda_stream
+
+        def check(rc):
+            if rc != 0:
+                raise RuntimeError(f"ceiling kernel launch failed with hipError {rc}")
+
+        def best(launch):
+            found = None
+            for groups in (256, 512, 1024, 2048):
+                for nt in (0, 1):
+                    us = spread(event_samples_us(torch, lambda: check(launch(groups, nt)), iters, warmup=2))["median"]
+                    if found is None or us < found[0]:
+                        found = (us, groups, nt)
+            return found
+        r_us, r_groups, r_nt = best(lambda g, nt: lib.ceiling_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), g, nt, stream()))
+        c_us, c_groups, c_nt = best(lambda g, nt: lib.ceiling_stream_copy(src.data_ptr(), dst.data_ptr(), nbytes, g, nt, stream()))
+        mfma = {}
+        for label, mfma_iters in (("burst", 100), ("sustained", 2000)):          # ~0.1 ms and ~1.5 ms per launch
+            groups = 256 * 8                                                     # eight wavefronts per SIMD
+            us = spread(event_samples_us(
+                torch, lambda: check(lib.ceiling_mfma_loop(mfma_iters, groups, sink.data_ptr(), stream())), iters, warmup=2))["median"]
+            mfma[label] = lib.ceiling_mfma_flops(mfma_iters, groups) / us / 1e6
+        del src, dst
+        return {"hbm_read_gbs": nbytes / r_us / 1e3, "hbm_read_shape": {"groups": r_groups, "nontemporal": bool(r_nt)},
+                "hbm_copy_gbs": 2 * nbytes / c_us / 1e3, "hbm_copy_shape": {"groups": c_groups, "nontemporal": bool(c_nt)},
+                "mfma_f16_tflops": mfma["sustained"], "mfma_f16_tflops_burst": mfma["burst"], "buffer_gib": gib,
+                "note": "1 GiB streaming read / copy (copy counts read + written bytes) and a register-resident "
+                        "v_mfma_f32_16x16x32_f16 loop (eight chains per wavefront, eight wavefronts per SIMD); HIP-event "
+                        "medians; the MFMA rate is limited by the clock the chip holds under that load"}
+
+
+class ColdSets:
+    """`sets` copies of every buffer of a workload, launched one after the other inside one graph, so that by
+    the time a copy comes round again the others have pushed it out of the L2s and the 256 MB Infinity Cache."""
+
+    def __init__(self, w, sets: int, fill_mode: int = 0):
+        self.paths = [Path(w, fill_mode) for _ in range(sets)]
+        self.sets = sets
+
+    def time_us(self, torch, what: str = "one_launch", iters: int = 20):
+        def all_sets():
+            for p in self.paths:
+                getattr(p, what)()
+        all_sets()
+        torch.cuda.synchronize()
+        g = capture(torch, all_sets)
+        return spread([t / self.sets for t in event_samples_us(torch, g.replay, iters)])
+
+
+def config_point(torch, w, steps: int = 200, blocks: int = 7):
+    """Compact record of one benchmark configuration: ragged_attn alone and the whole step in one launch
+    (kernel time inside a graph, HBM fraction of the algorithmic bytes), and the wall-clock step on one stream."""
+    p = Path(w, 0)
+    p.pack()                                          # cu_seqlens for the attention launches below
+    torch.cuda.synchronize()
+    alg = p.algorithmic()
+    attn = kernel_time_us(torch, p.attn, iters=20)
+    step = kernel_time_us(torch, p.one_launch, iters=20)
+    wall = wall_blocks(torch, p.prepared_one_launch(), steps, blocks)
+    frac = lambda name, us: alg[name]["bytes"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
+    return {"workload": w.name, "dtype": w.dtype, "B": w.B, "N": w.N, "T": w.T, "max_len": max(w.lengths),
+            "attn_us": attn["median"], "attn_hbm_frac": frac("attn", attn["median"]),
+            "attn_tflops": alg["attn"]["flops"] / attn["median"] / 1e6,
+            "step_kernel_us": step["median"], "step_hbm_frac": frac("pack_attn_unpack", step["median"]),
+            "step_wall_us": wall["median"] * 1e6, "step_tokens_per_s": w.T / wall["median"]}
+
+
+def pipeline_point(torch, pipe, kernels: int, alg_bytes: int | None = None):
+    """A whole multi-layer loop captured in one HIP graph: GPU time of a replay, wall-clock per replay, tokens/s."""
+    pipe.run()
+    torch.cuda.synchronize()
+    g = capture(torch, pipe.run)
+    gpu = spread(event_samples_us(torch, g.replay, 30))
+    wall = spread([wall_steps(torch, g.replay, 50) for _ in range(7)])
+    rec = {"kernels_in_graph": kernels, "tokens": pipe.tokens, "graph_gpu_us": gpu["median"],
+           "graph_gpu_us_p10_p90": [gpu["p10"], gpu["p90"]], "graph_wall_us": wall["median"] * 1e6,
+           "tokens_per_s": pipe.tokens / wall["median"]}
+    if alg_bytes:
+        rec["hbm_frac"] = alg_bytes / (gpu["median"] * 1e-6) / 1e9 / HBM_PEAK_GBS
+    return rec
