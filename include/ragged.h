@@ -76,7 +76,8 @@ int ragged_pack(const void* x, const uint8_t* keep, int B, int N, int C, ragged_
  *   cu_seqlens [B + 1]     as written by ragged_pack
  *   max_seqlen             host-known upper bound on every n_i (N always works); it only sizes
  *                          the grid.  Query rows at positions >= max_seqlen inside an image are
- *                          NOT computed, so a bound that is too small loses rows.
+ *                          NOT computed, so a bound that is too small loses rows (ragged_attn_checked
+ *                          reports that case on the device).
  *   scale                  finite fp32 softmax scale (the paper uses 1/sqrt(D))
  *
  * Supported: D = 64; (in_dt, out_dt) in {F16->F16, F16->F32, BF16->BF16, BF16->F32}.
@@ -106,6 +107,26 @@ int ragged_attn_strided(const void* q, const void* k, const void* v, void* o,
                         const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
                         int64_t in_tok_stride, int64_t out_tok_stride, float scale,
                         ragged_dtype in_dt, ragged_dtype out_dt, void* stream);
+
+/*
+ * ragged_attn_checked -- ragged_attn_strided that also reports a `max_seqlen` that was too small.
+ * Section 4.2 sizes its grid from the host-known sequence bound; here that bound is an argument, a bound
+ * below some n_i silently leaves query rows of that image uncomputed, and the host cannot see n_i without
+ * the synchronisation this library avoids.  This entry point closes the gap on the device:
+ *
+ *   flags      [1]  int32, caller-zeroed.  Bit 0 (RAGGED_FLAG_SEQLEN_EXCEEDED) is OR-ed in when some image
+ *                   has n_i > max_seqlen.  The library never clears it; the caller reads it whenever it
+ *                   next synchronises (or never).
+ *
+ * Query rows at positions >= 64 * ceil(max_seqlen / 64) of an offending image are not computed (their rows
+ * of `o` stay untouched); every other row of the batch is computed as by ragged_attn_strided, bit for bit.
+ * ragged_pack_attn_unpack and ragged_attn_padded size their grids from N itself and can never lose a row.
+ */
+#define RAGGED_FLAG_SEQLEN_EXCEEDED 1
+int ragged_attn_checked(const void* q, const void* k, const void* v, void* o,
+                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
+                        int64_t in_tok_stride, int64_t out_tok_stride, float scale,
+                        ragged_dtype in_dt, ragged_dtype out_dt, int32_t* flags, void* stream);
 
 /*
  * ragged_unpack -- the inverse scatter of ragged_pack (the paper names the stage in its

@@ -19,7 +19,7 @@ RAGGED_OK = 0
 RAGGED_F16, RAGGED_BF16, RAGGED_F32 = 0, 1, 2
 _DTYPE_CODE = {torch.float16: RAGGED_F16, torch.bfloat16: RAGGED_BF16, torch.float32: RAGGED_F32}
 
-EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_strided", "ragged_attn_padded", "ragged_unpack",
+EXPORTS = ("ragged_pack", "ragged_attn", "ragged_attn_strided", "ragged_attn_checked", "ragged_attn_padded", "ragged_unpack",
            "ragged_repack", "ragged_cls_extract", "ragged_pack_attn_unpack", "ragged_linear", "ragged_layernorm",
            "ragged_token_scores_l2", "ragged_keep_topk", "ragged_noop", "ragged_status_string", "ragged_version")
 
@@ -48,6 +48,8 @@ def load() -> ctypes.CDLL:
         lib.ragged_attn.restype = i32
         lib.ragged_attn_strided.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, f32, i32, i32, vp]
         lib.ragged_attn_strided.restype = i32
+        lib.ragged_attn_checked.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, f32, i32, i32, vp, vp]
+        lib.ragged_attn_checked.restype = i32
         lib.ragged_repack.argtypes = [vp, vp, vp, i32, i64, i32, i32, vp, i64, vp, vp, vp]
         lib.ragged_repack.restype = i32
         lib.ragged_cls_extract.argtypes = [vp, vp, i32, i32, i32, vp, vp]
@@ -171,6 +173,16 @@ def ragged_attn_strided(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, s
     [rows,3,H,D] QKV buffer; o may be a strided view too."""
     _check("ragged_attn_strided",
            load().ragged_attn_strided(*_attn_strided_args(q, k, v, o, cu_seqlens, max_seqlen, scale, stream)))
+
+
+FLAG_SEQLEN_EXCEEDED = 1
+
+
+def ragged_attn_checked(q, k, v, o, cu_seqlens, max_seqlen: int, scale: float, flags, stream=None) -> None:
+    """ragged_attn_strided that ORs FLAG_SEQLEN_EXCEEDED into flags[0] (int32 GPU tensor, zeroed by the caller)
+    when some image holds more than max_seqlen tokens."""
+    args = _attn_strided_args(q, k, v, o, cu_seqlens, max_seqlen, scale, stream)
+    _check("ragged_attn_checked", load().ragged_attn_checked(*args[:-1], _dev(flags, "flags", torch.int32), args[-1]))
 
 
 def _repack_args(packed_in, keep_rows, cu_in, packed_out, cu_out, gather_out, stream):

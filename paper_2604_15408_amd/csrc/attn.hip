@@ -246,6 +246,8 @@ struct StepArgs {
     int32_t* cu_seqlens;        // [B + 1]
     int32_t* gather_idx;        // [cap_rows]
     int64_t cap_rows;
+    int32_t* flags;             // MODE kPacked only, may be null: bit 0 is set when some n_i > max_seqlen
+    int max_seqlen;
 };
 
 template <typename In, typename OutT, int MODE>
@@ -285,16 +287,23 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int m0 = m_tile * kBM;
 
     __shared__ uint16_t idx_lds[LIST ? kMaxGatherTokens : 1];      // kept token positions, ascending
-    __shared__ int wave_cnt[WAVES];
+    constexpr int kRounds = kMaxGatherTokens / kAttnThreads;       // mask bytes per thread: all requested up front
+    __shared__ int wave_cnt[LIST ? kRounds * WAVES : 1];
     __shared__ int lds4[4];
     int s, n;
     if (LIST) {
         constexpr int kThreads = kAttnThreads;
-        constexpr int kPre = 4;                                // mask bytes per thread requested up front
+        static_assert(kRounds * kThreads == kMaxGatherTokens, "the mask of an image is read in whole rounds of the group");
         const uint8_t* mask = keep + (int64_t)img * n_tok;
         s = img * n_tok;
         PrefixLoads before_image;
         if (MODE == kStep) before_image = prefix_issue(keep, img * n_tok);   // requested with the image's own mask
+        bool pre[kRounds];
+#pragma unroll
+        for (int j = 0; j < kRounds; ++j) {
+            const int t = j * kThreads + tid;
+            pre[j] = t < n_tok && mask[t] != 0;
+        }
         if (fill_mode == 1 && m_tile == 0) {                   // zero this head's slice of dropped rows
             if (MODE == kStep) {
                 for (int t = tid / 8; t < n_tok; t += kThreads / 8)
@@ -308,48 +317,52 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                         reinterpret_cast<uint4*>(o + (s + t) * tok_o + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
             }
         }
-        bool pre[kPre];
+        // Count first (one barrier): a group learns the image's length n before anything else is built, and
+        // the groups of the upper-bound grid that have no rows leave here.
+        uint64_t bits[kRounds];
 #pragma unroll
-        for (int j = 0; j < kPre; ++j) {
-            const int t = j * kThreads + tid;
-            pre[j] = t < n_tok && mask[t] != 0;
-        }
-        n = 0;
-        auto append = [&](bool kept, int t) {                  // every thread of the group calls this
-            const uint64_t bits = __ballot(kept);
-            if (lane == 0) wave_cnt[wave] = __popcll(bits);
-            __syncthreads();
-            int before = n, total = 0;
-#pragma unroll
-            for (int w2 = 0; w2 < WAVES; ++w2) {
-                const int c = wave_cnt[w2];
-                before += w2 < wave ? c : 0;
-                total += c;
+        for (int j = 0; j < kRounds; ++j)
+            if (j * kThreads < n_tok) {                        // group-uniform
+                bits[j] = __ballot(pre[j]);
+                if (lane == 0) wave_cnt[j * WAVES + wave] = __popcll(bits[j]);
             }
-            if (kept) idx_lds[before + __popcll(bits & ((1ull << lane) - 1ull))] = (uint16_t)t;
-            n += total;
-            __syncthreads();
-        };
+        __syncthreads();
+        n = 0;
+        int before[kRounds];                                   // kept tokens in front of this wavefront's 64 of round j
 #pragma unroll
-        for (int j = 0; j < kPre; ++j)
-            if (j * kThreads < n_tok) append(pre[j], j * kThreads + tid);
-        for (int base = kPre * kThreads; base < n_tok; base += kThreads) {
-            const int t = base + tid;
-            append(t < n_tok && mask[t] != 0, t);
-        }
+        for (int j = 0; j < kRounds; ++j)
+            if (j * kThreads < n_tok) {
+                before[j] = n;
+#pragma unroll
+                for (int w2 = 0; w2 < WAVES; ++w2) {
+                    const int c = wave_cnt[j * WAVES + w2];
+                    before[j] += w2 < wave ? c : 0;
+                    n += c;
+                }
+            }
+        n = __builtin_amdgcn_readfirstlane(n);
+        // a group with no rows that does not write cu_seqlens either is done (whole group, before any further barrier)
+        if (m0 >= n && !(MODE == kStep && h == 0 && m_tile == 0)) return;
+#pragma unroll
+        for (int j = 0; j < kRounds; ++j)
+            if (j * kThreads < n_tok && pre[j])
+                idx_lds[before[j] + __popcll(bits[j] & ((1ull << lane) - 1ull))] = (uint16_t)(j * kThreads + tid);
         if (MODE == kStep) {
-            // a group with no rows that does not write cu_seqlens either is done (whole group, before the barrier)
-            if (m0 >= n && !(h == 0 && m_tile == 0)) return;
-            s = prefix_finish(keep, before_image, lds4);       // kept tokens of the images before this one
-            s = __builtin_amdgcn_readfirstlane(s);
+            s = prefix_finish(keep, before_image, lds4);       // kept tokens of the images before this one; its
+            s = __builtin_amdgcn_readfirstlane(s);             // barrier also publishes idx_lds
             if (h == 0 && m_tile == 0 && tid == 0) {
                 if (img == 0) step.cu_seqlens[0] = 0;
                 step.cu_seqlens[img + 1] = s + n;
             }
+        } else {
+            __syncthreads();                                   // idx_lds complete
         }
     } else {
         s = cu_seqlens[img];
         n = cu_seqlens[img + 1] - s;
+        // the caller's bound was too small for this image: say so (one group per image; a vector atomic)
+        if (step.flags != nullptr && h == 0 && m_tile == 0 && tid == 0 && n > step.max_seqlen)
+            atomicOr(step.flags, RAGGED_FLAG_SEQLEN_EXCEEDED);
     }
     n = __builtin_amdgcn_readfirstlane(n);
     if (m0 >= n) return;                                       // whole group exits together
@@ -541,9 +554,12 @@ hipError_t launch_any(const void* q, const void* k, const void* v, void* o, cons
 hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, int64_t in_tok,
                        int64_t out_tok, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
-                       hipStream_t stream) {
+                       int32_t* flags, hipStream_t stream) {
+    StepArgs extra{};
+    extra.flags = flags;
+    extra.max_seqlen = max_seqlen;
     return launch_any<kPacked>(q, k, v, o, cu_seqlens, nullptr, 0, 0, B, max_seqlen, H, in_tok, out_tok, scale,
-                               in_dt, out_dt, StepArgs{}, stream);
+                               in_dt, out_dt, extra, stream);
 }
 
 int attn_padded_max_tokens() { return kMaxGatherTokens; }
@@ -562,7 +578,7 @@ hipError_t launch_step(const void* x, const uint8_t* keep, const void* q, const 
                        hipStream_t stream) {
     const int64_t tok = (int64_t)H * kHeadDim;
     const StepArgs step{static_cast<const uint16_t*>(x), static_cast<uint16_t*>(packed),
-                        static_cast<uint16_t*>(out), cu_seqlens, gather_idx, cap_rows};
+                        static_cast<uint16_t*>(out), cu_seqlens, gather_idx, cap_rows, nullptr, 0};
     if (dt == RAGGED_F16)
         return launch_typed<F16, _Float16, kStep>(q, k, v, o, nullptr, keep, N, fill_mode, B, N, H, tok, tok, scale,
                                                   step, stream);

@@ -36,7 +36,7 @@ hipError_t launch_unpack(const void* src, const uint8_t* keep, const int32_t* cu
 hipError_t launch_attn(const void* q, const void* k, const void* v, void* o,
                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, int64_t in_tok,
                        int64_t out_tok, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
-                       hipStream_t stream);
+                       int32_t* flags, hipStream_t stream);
 hipError_t launch_attn_padded(const void* q, const void* k, const void* v, void* o, const uint8_t* keep,
                               int B, int N, int H, float scale, ragged_dtype in_dt, ragged_dtype out_dt,
                               int fill_mode, hipStream_t stream);

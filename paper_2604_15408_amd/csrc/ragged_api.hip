@@ -7,7 +7,7 @@
 
 namespace {
 
-constexpr int kVersion = 700;  // 0.7.0
+constexpr int kVersion = 800;  // 0.8.0
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_BF16; }
@@ -16,6 +16,32 @@ inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_B
 inline bool rows_fit(int B, int N) { return (int64_t)B * N <= (int64_t)INT32_MAX; }
 
 inline int from_hip(hipError_t e) { return e == hipSuccess ? RAGGED_OK : RAGGED_ERR_HIP; }
+
+// ragged_attn, ragged_attn_strided and ragged_attn_checked share the checks and the launch; flags may be null
+int attn_call(const void* q, const void* k, const void* v, void* o,
+              const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
+              int64_t in_tok_stride, int64_t out_tok_stride, float scale,
+              ragged_dtype in_dt, ragged_dtype out_dt, int32_t* flags, void* stream) {
+    if (!q || !k || !v || !o || !cu_seqlens) return RAGGED_ERR_NULL;
+    if (B <= 0 || H <= 0 || D <= 0 || max_seqlen < 1) return RAGGED_ERR_SHAPE;
+    // grid <= q-tiles * (B*H rounded up to a whole dispatch batch of 512) must fit a 32-bit grid
+    const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)max_seqlen + 63) / 64);
+    if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
+    const int64_t row = (int64_t)H * D;
+    // the kernel addresses the 64 rows of a K/V tile with 32-bit byte offsets
+    if (in_tok_stride < row || out_tok_stride < row || in_tok_stride > (int64_t)1 << 23) return RAGGED_ERR_SHAPE;
+    if (D != 64) return RAGGED_ERR_UNSUPPORTED;
+    const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
+                         (in_dt == RAGGED_BF16 && (out_dt == RAGGED_BF16 || out_dt == RAGGED_F32));
+    if (!pair_ok || !isfinite(scale)) return RAGGED_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return RAGGED_ERR_UNSUPPORTED;
+    // every token row must start on a 16-byte boundary
+    const int64_t out_bytes = out_dt == RAGGED_F32 ? 4 : 2;
+    if ((in_tok_stride * 2) % 16 != 0 || (out_tok_stride * out_bytes) % 16 != 0) return RAGGED_ERR_UNSUPPORTED;
+    return from_hip(ragged::launch_attn(q, k, v, o, cu_seqlens, B, max_seqlen, H, in_tok_stride,
+                                        out_tok_stride, scale, in_dt, out_dt, flags,
+                                        static_cast<hipStream_t>(stream)));
+}
 
 }  // namespace
 
@@ -36,25 +62,18 @@ int ragged_attn_strided(const void* q, const void* k, const void* v, void* o,
                         const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
                         int64_t in_tok_stride, int64_t out_tok_stride, float scale,
                         ragged_dtype in_dt, ragged_dtype out_dt, void* stream) {
-    if (!q || !k || !v || !o || !cu_seqlens) return RAGGED_ERR_NULL;
-    if (B <= 0 || H <= 0 || D <= 0 || max_seqlen < 1) return RAGGED_ERR_SHAPE;
-    // grid <= q-tiles * (B*H rounded up to a whole dispatch batch of 512) must fit a 32-bit grid
-    const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)max_seqlen + 63) / 64);
-    if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
-    const int64_t row = (int64_t)H * D;
-    // the kernel addresses the 64 rows of a K/V tile with 32-bit byte offsets
-    if (in_tok_stride < row || out_tok_stride < row || in_tok_stride > (int64_t)1 << 23) return RAGGED_ERR_SHAPE;
-    if (D != 64) return RAGGED_ERR_UNSUPPORTED;
-    const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
-                         (in_dt == RAGGED_BF16 && (out_dt == RAGGED_BF16 || out_dt == RAGGED_F32));
-    if (!pair_ok || !isfinite(scale)) return RAGGED_ERR_UNSUPPORTED;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return RAGGED_ERR_UNSUPPORTED;
-    // every token row must start on a 16-byte boundary
-    const int64_t out_bytes = out_dt == RAGGED_F32 ? 4 : 2;
-    if ((in_tok_stride * 2) % 16 != 0 || (out_tok_stride * out_bytes) % 16 != 0) return RAGGED_ERR_UNSUPPORTED;
-    return from_hip(ragged::launch_attn(q, k, v, o, cu_seqlens, B, max_seqlen, H, in_tok_stride,
-                                        out_tok_stride, scale, in_dt, out_dt,
-                                        static_cast<hipStream_t>(stream)));
+    return attn_call(q, k, v, o, cu_seqlens, B, max_seqlen, H, D, in_tok_stride, out_tok_stride, scale, in_dt,
+                     out_dt, nullptr, stream);
+}
+
+int ragged_attn_checked(const void* q, const void* k, const void* v, void* o,
+                        const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
+                        int64_t in_tok_stride, int64_t out_tok_stride, float scale,
+                        ragged_dtype in_dt, ragged_dtype out_dt, int32_t* flags, void* stream) {
+    if (!flags) return RAGGED_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(flags) & 3u) != 0) return RAGGED_ERR_UNSUPPORTED;
+    return attn_call(q, k, v, o, cu_seqlens, B, max_seqlen, H, D, in_tok_stride, out_tok_stride, scale, in_dt,
+                     out_dt, flags, stream);
 }
 
 int ragged_attn(const void* q, const void* k, const void* v, void* o,

@@ -105,6 +105,18 @@ def test_attn_strided_validation(lib):
         assert call(**bad) == 3
 
 
+def test_attn_checked_validation(lib):
+    def call(q=FAKE, k=FAKE, v=FAKE, o=FAKE, cu=FAKE, B=2, ms=8, H=2, D=64, si=128, so=128, scale=0.125, i=0, od=0,
+             flags=FAKE):
+        return lib.ragged_attn_checked(q, k, v, o, cu, B, ms, H, D, si, so, scale, i, od, flags, None)
+    for null in ("q", "k", "v", "o", "cu", "flags"):
+        assert call(**{null: None}) == 1
+    for bad in (dict(B=0), dict(ms=0), dict(si=64)):
+        assert call(**bad) == 2
+    for bad in (dict(D=32), dict(flags=FAKE + 2), dict(i=0, od=1), dict(scale=float("nan"))):
+        assert call(**bad) == 3
+
+
 def test_repack_validation(lib):
     def call(src=FAKE, kr=FAKE, cu=FAKE, B=2, cap_in=16, C=64, dt=0, dst=FAKE, cap_out=16, cuo=FAKE, gi=FAKE):
         return lib.ragged_repack(src, kr, cu, B, cap_in, C, dt, dst, cap_out, cuo, gi, None)

@@ -37,6 +37,10 @@ def check(lengths, H, dtype, seed, scale=0.125, out_dtype=None, max_seqlen=None,
     err = np.abs(got[:T] - want)
     bound = tol + (np.abs(want) * 2.0 ** -8 if raw.dtype == torch.bfloat16 else 0.0)
     assert np.all(err <= bound), f"max abs err {err.max():.3e} (lengths={lengths[:8]}..)"
+    if raw.dtype == torch.bfloat16:
+        # bf16 output = the fp32-output result (held to the strict bar by the callers that ask for it) rounded once
+        _, raw32 = hp.gpu_attn(q, k, v, cu, ms, scale, torch.float32, extra_rows=3)
+        assert torch.equal(raw[:T].view(torch.int16), raw32[:T].to(torch.bfloat16).view(torch.int16))
     return float(err.max()) if T else 0.0
 
 
@@ -102,10 +106,15 @@ def test_sweep_bf16_fp32_out(p):
     q, k, v = w.qkv()
     cu = hp.cu_from_lengths(w.lengths)
     want = oracle.attn(wl.to_words(q), wl.to_words(k), wl.to_words(v), cu, w.scale, "bf16", threads=8)
-    got, _ = hp.gpu_attn(q, k, v, cu, w.N, w.scale, out_dtype=torch.float32)
+    got, raw32 = hp.gpu_attn(q, k, v, cu, w.N, w.scale, out_dtype=torch.float32)
     assert np.max(np.abs(got - want)) <= TOL
-    got, _ = hp.gpu_attn(q, k, v, cu, w.N, w.scale)           # bf16 out: output rounding added
+    got, raw16 = hp.gpu_attn(q, k, v, cu, w.N, w.scale)       # bf16 out: output rounding added
     assert np.all(np.abs(got - want) <= TOL + np.abs(want) * 2.0 ** -8)
+    # the bf16-output path is the strictly checked fp32-output path plus ONE round-to-nearest-even
+    assert torch.equal(raw16.view(torch.int16), raw32.to(torch.bfloat16).view(torch.int16))
+    # where the output rounding is small next to the bar (|o| < 1/4: half an ulp <= 2^-11) the strict bar holds
+    small = np.abs(want) < 0.25
+    assert np.all(np.abs(got - want)[small] <= TOL)
 
 
 @pytest.mark.parametrize("B", [1, 2, 4, 32])
@@ -191,6 +200,48 @@ def test_max_seqlen_only_bounds_the_grid():
     _, a = hp.gpu_attn(q, k, v, cu, 64, 0.125)
     _, b = hp.gpu_attn(q, k, v, cu, 1000, 0.125)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def _checked(lengths, bound, H=2, seed=606):
+    """ragged_attn_checked on sentinel-filled output; returns (raw output, flags word, inputs)."""
+    from paper_2604_15408_amd import binding
+    cu = hp.cu_from_lengths(lengths)
+    q, k, v = _qkv(int(cu[-1]), H, "f16", seed)
+    dev = "cuda:0"
+    o = torch.full(q.shape, 77.0, dtype=q.dtype, device=dev)
+    flags = torch.zeros(1, dtype=torch.int32, device=dev)
+    binding.ragged_attn_checked(q.to(dev), k.to(dev), v.to(dev), o, torch.from_numpy(cu).to(dev), bound, 0.125, flags)
+    torch.cuda.synchronize()
+    return o.cpu(), int(flags.item()), (q, k, v, cu)
+
+
+def test_checked_attention_reports_a_bound_that_is_too_small():
+    """max_seqlen below some n_i: the flag bit is set on the device, every kernel exits normally, the rows the
+    grid does cover equal ragged_attn's bit for bit, and the rows it does not cover stay untouched."""
+    from paper_2604_15408_amd import binding
+    lengths = [30, 150, 10, 64]
+    raw, flags, (q, k, v, cu) = _checked(lengths, bound=64)         # image 1 has 150 > 64 tokens
+    assert flags & binding.FLAG_SEQLEN_EXCEEDED
+    _, full = hp.gpu_attn(q, k, v, cu, 150, 0.125)
+    a, b = raw.view(torch.int16), full.view(torch.int16)
+    covered = np.ones(int(cu[-1]), dtype=bool)
+    covered[cu[1] + 64: cu[2]] = False                               # query rows 64.. of image 1 are lost
+    assert torch.equal(a[covered], b[covered])
+    assert bool((raw[~covered] == 77.0).all())
+
+
+def test_checked_attention_keeps_the_flag_clear_when_the_bound_holds():
+    lengths = [30, 150, 10, 64]
+    for bound in (150, 197, 1000):
+        raw, flags, (q, k, v, cu) = _checked(lengths, bound=bound)
+        assert flags == 0
+        _, full = hp.gpu_attn(q, k, v, cu, bound, 0.125)
+        assert torch.equal(raw.view(torch.int16), full.view(torch.int16))
+    # a bound between n_i and the next multiple of 64 loses nothing but is still reported: 150 > 140
+    raw, flags, (q, k, v, cu) = _checked(lengths, bound=140)
+    assert flags == 1
+    _, full = hp.gpu_attn(q, k, v, cu, 150, 0.125)
+    assert torch.equal(raw.view(torch.int16), full.view(torch.int16))
 
 
 def test_permutation_equivariance_within_tolerance():

@@ -76,6 +76,40 @@ def test_twelve_layer_loop_in_one_graph_matches_eager_and_oracle():
     assert not pipe.x[-1][~w.keep.bool().to("cuda:0")].any()
 
 
+def test_full_size_twelve_layer_graph_against_the_oracle():
+    """The 12-layer configuration at its full size (B = 64, N = 197, C = 768), one replay of the one-graph loop:
+    cu_seqlens of every layer exactly, sampled attention rows of layers 3, 6, 9 and 12 (the layers that prune, and
+    the last) against the oracle one row at a time, and the final unpack bit for bit."""
+    layers = wl.pipeline()
+    assert layers[0].B == 64 and len(layers) == 12
+    pipe = Pipeline(layers, fill_mode=1)
+    pipe.run()                                              # warms the code path; capture() runs it once more
+    g = capture(torch, pipe.run)
+    for t in pipe.x[1:] + pipe.o:
+        t.fill_(9.0)
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    for l, w in enumerate(layers):
+        assert pipe.cu[l].cpu().numpy().tolist() == hp.cu_from_lengths(w.lengths).tolist()
+    rng = np.random.default_rng(11)
+    for l in (2, 5, 8, 11):
+        w = layers[l]
+        q, k, v = (wl.to_words(t) for t in w.qkv())
+        cu = hp.cu_from_lengths(w.lengths)
+        got = pipe.o[l][: w.T].cpu().to(torch.float64).numpy()
+        assert np.all(np.isfinite(got))
+        for _ in range(60):
+            i, h = int(rng.integers(w.B)), int(rng.integers(w.H))
+            r = int(rng.integers(cu[i + 1] - cu[i]))
+            _, o = oracle.attn_row(q, k, v, cu, i, h, r, w.scale, "f16")
+            assert np.max(np.abs(got[cu[i] + r, h] - o)) <= 2e-3
+    w = layers[-1]
+    cu = hp.cu_from_lengths(w.lengths)
+    want_x = oracle.unpack(wl.to_words(pipe.o[-1][: w.T].cpu()).reshape(w.T, w.C), w.keep.numpy(), cu, w.C, 1)
+    assert np.array_equal(wl.to_words(pipe.x[-1].cpu()), want_x)
+
+
 def test_stay_packed_loop_matches_the_unpack_pack_loop_and_oracle():
     """Pack once, stay packed (strided attention, re-pack at the pruning layers, CLS read at the end):
     same lengths and attention rows as the loop that goes through the padded tensor every layer."""
