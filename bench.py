@@ -123,9 +123,9 @@ def run(args):
         for _ in range(args.warmup):
             fn()
         if name.startswith("streams3"):               # events on one stream see only a third of these launches
-            t_modes[name] = wall_blocks(torch, fn, args.steps)
+            t_modes[name] = wall_blocks(torch, fn, args.steps, args.blocks)
         else:
-            t_modes[name], gpu_modes[name] = timed_blocks(torch, fn, args.steps)
+            t_modes[name], gpu_modes[name] = timed_blocks(torch, fn, args.steps, args.blocks)
     t_step = t_modes[HEADLINE_MODE]["median"]
 
     # ---- each kernel alone: REPLICAS back-to-back copies in one graph, HIP events around each replay
@@ -196,7 +196,7 @@ def run(args):
         "config": {"workload": w.name, "B": w.B, "N": w.N, "H": w.H, "D": w.D, "T": w.T,
                    "max_len": max(w.lengths), "lengths": w.note, "launch": HEADLINE_MODE,
                    "streams": 1, "unpack_fill_mode": args.fill_mode},
-        "timing": {"blocks": BLOCKS, "steps_per_block": block_steps(args.steps),
+        "timing": {"blocks": args.blocks, "steps_per_block": block_steps(args.steps),
                    "ms_per_step_p10": t_modes[HEADLINE_MODE]["p10"] * 1e3,
                    "ms_per_step_p90": t_modes[HEADLINE_MODE]["p90"] * 1e3,
                    "note": "value and ms_per_step are the median over the blocks; each block is a multiple of "
@@ -240,6 +240,8 @@ def main():
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--fill-mode", type=int, default=0, choices=(0, 1))
     ap.add_argument("--report", default=None, help="also write the JSON to this path")
+    ap.add_argument("--blocks", type=int, default=BLOCKS,
+                    help="timed blocks per way of issuing the step (median / p10 / p90 are taken over them)")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the compact block on the other benchmark configurations (used under the profiler)")
     ap.add_argument("--calibrate-copy", action="store_true",
