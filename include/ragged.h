@@ -82,7 +82,12 @@ int ragged_pack(const void* x, const uint8_t* keep, int B, int N, int C, ragged_
  *
  * Supported: D = 64; (in_dt, out_dt) in {F16->F16, F16->F32, BF16->BF16, BF16->F32}.
  * Contractions run on MFMA with fp32 accumulation; the softmax runs in fp32.
- * Images with n_i = 0 produce no rows.  Results are bit-reproducible from run to run.
+ * Images with n_i = 0 produce no rows.  Results are bit-reproducible from run to run with the same arguments.
+ * The launch shape follows B, H and max_seqlen (small launches split the keys of a sequence over the wavefronts
+ * of a work-group and merge the partial results, large ones walk them in order), so the bits of a sequence
+ * longer than 64 tokens may differ in the last place between calls with different B, H or max_seqlen; all the
+ * entry points of this header take the same shape for the same (B, H, bound), so they stay bit-identical to
+ * each other.
  */
 int ragged_attn(const void* q, const void* k, const void* v, void* o,
                 const int32_t* cu_seqlens, int B, int max_seqlen, int H, int D,
@@ -118,8 +123,9 @@ int ragged_attn_strided(const void* q, const void* k, const void* v, void* o,
  *                   has n_i > max_seqlen.  The library never clears it; the caller reads it whenever it
  *                   next synchronises (or never).
  *
- * Query rows at positions >= 64 * ceil(max_seqlen / 64) of an offending image are not computed (their rows
- * of `o` stay untouched); every other row of the batch is computed as by ragged_attn_strided, bit for bit.
+ * Query rows at positions >= max_seqlen of an offending image may be left uncomputed (such a row of `o` then stays
+ * untouched as a whole; rows at positions >= 64 * ceil(max_seqlen / 64) always do); every other row of the batch is
+ * computed as by ragged_attn_strided with the same arguments, bit for bit.
  * ragged_pack_attn_unpack and ragged_attn_padded size their grids from N itself and can never lose a row.
  */
 #define RAGGED_FLAG_SEQLEN_EXCEEDED 1

@@ -57,6 +57,7 @@ constexpr int kAttnOcc = kAttnWaves == 8 ? 2 : (kRing == 2 ? 4 : (kRing == 3 ? 3
 constexpr int kTileBytes = kBN * kHeadDim * 2;   // one K or one V tile: 8 KB
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazyLog2 = 8.0f;       // probabilities stay below 2^8 between rescales
+constexpr int kSplitMaxGroups = 256;    // launches of at most this many 64-row q-tiles split the keys over the wavefronts
 constexpr int kMaxGatherTokens = 1536;  // tokens per image the gather-on-load variant can index in LDS
 
 // O^T += V^T P^T for one 32-key block: p[0..7] are this lane's probabilities (fp32).  The row sums
@@ -109,6 +110,21 @@ __device__ __forceinline__ void store16(float* dst, const float (&v)[16]) {
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         reinterpret_cast<float4*>(dst)[e] = make_float4(v[4 * e], v[4 * e + 1], v[4 * e + 2], v[4 * e + 3]);
+}
+
+// Store 4 consecutive head-dim elements of one output row.
+__device__ __forceinline__ void store4(_Float16* dst, const float (&v)[4]) {
+    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+    const f16x4 a = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+    *reinterpret_cast<uint2*>(dst) = __builtin_bit_cast(uint2, a);
+}
+__device__ __forceinline__ void store4(__bf16* dst, const float (&v)[4]) {
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    const bf16x4 a = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+    *reinterpret_cast<uint2*>(dst) = __builtin_bit_cast(uint2, a);
+}
+__device__ __forceinline__ void store4(float* dst, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
 }
 
 // Reductions over the four lanes that share a query (l, l^16, l^32, l^48) with the gfx950 lane-swap
@@ -250,8 +266,14 @@ struct StepArgs {
     int max_seqlen;
 };
 
-template <typename In, typename OutT, int MODE>
-__global__ __launch_bounds__(kAttnThreads, kAttnOcc < 1 ? 1 : kAttnOcc)
+// SPLIT (small launches, where a work-group has a CU to itself and the path is a chain of latencies):
+//   the work-group takes only 16 queries and its four wavefronts split the KEYS instead -- wavefront w
+//   loads K/V tiles w, w+4, ... into a slot of its own (no barrier in the loop) and runs the same tile
+//   arithmetic on them; the four partial results (running maximum, row sum, accumulators) are merged
+//   through LDS at the end, each wavefront finishing four of the sixteen head-dim elements a lane owns.
+//   A sequence of up to 256 tokens then costs one tile time plus the merge instead of up to four.
+template <typename In, typename OutT, int MODE, bool SPLIT>
+__global__ __launch_bounds__(kAttnThreads, SPLIT ? 2 : (kAttnOcc < 1 ? 1 : kAttnOcc))
 void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                  const uint16_t* __restrict__ v, OutT* __restrict__ o,
                  const int32_t* __restrict__ cu_seqlens, const uint8_t* __restrict__ keep, int n_tok,
@@ -265,8 +287,8 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     constexpr int WAVES = kAttnWaves;
     constexpr int kI = 8 / WAVES;                              // load instructions per wavefront per K (or V) tile
     constexpr int kPer = 2 * kI;                               // ... per K+V tile
-    constexpr int kBM = 16 * WAVES;                            // queries per work-group
-    __shared__ __attribute__((aligned(1024))) uint4 ring[kRing * 2 * kTileBytes / 16];   // [slot][K|V]
+    constexpr int kBM = SPLIT ? 16 : 16 * WAVES;               // queries per work-group
+    __shared__ __attribute__((aligned(1024))) uint4 ring[(SPLIT ? WAVES : kRing) * 2 * kTileBytes / 16];   // [slot][K|V]
 
     // bid = (batch * q_tiles + m_tile) * group + slot ; pair = batch * group + slot
     const int per_batch = q_tiles * group;
@@ -369,7 +391,8 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int64_t pad0 = (int64_t)img * n_tok;                 // first padded row of the image (kStep)
     // row of the j-th token of this image in q / k / v / o
     auto row_of = [&](int j) -> int64_t { return GATHER ? (int64_t)s + idx_lds[j] : (int64_t)s + j; };
-    const bool wave_active = m0 + wave * 16 < n;               // wavefront has at least one real query
+    const int q_row = m0 + (SPLIT ? 0 : wave * 16) + col;      // this lane's query inside the image
+    const bool wave_active = SPLIT || m0 + wave * 16 < n;      // wavefront has at least one real query
 
     // ---- K/V tile loads.  Instruction i (0, 1) of this wavefront covers tile rows 16*wave + 8i + lane/8;
     // the lane's LDS slot is position lane%8 of that row, which holds chunk (lane%8) ^ ((row>>1)&3).
@@ -401,12 +424,35 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         return kPer;
     };
 
+    // SPLIT: the whole tile t into this wavefront's own slot (eight instructions per operand)
+    auto issue_own = [&](int t) {
+        const int rem = n - t * kBN;
+        const int need_rows = rem >= kBN ? kBN : 32 * ((rem + 31) >> 5);
+        const uint32_t dst = ring0 + wave * 2 * kTileBytes;
+        const int64_t tile_off = GATHER ? 0 : (int64_t)t * kBN * tok;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (8 * i < need_rows) {                            // wave-uniform
+                int rel = 8 * i + (lane >> 3);
+                rel = rel < rem ? rel : rem - 1;
+                const uint32_t row = GATHER ? (uint32_t)idx_lds[t * kBN + rel] : (uint32_t)rel;
+                const uint32_t voff = row * tok_bytes + load_chunk;
+                dma16(dst + i * 1024, voff, k_base + tile_off);
+                dma16(dst + i * 1024 + kTileBytes, voff, v_base + tile_off);
+            }
+        }
+    };
+
     const int tiles = (n + kBN - 1) / kBN;
     // c_next[d] = load instructions this wavefront has in flight for tile t+1+d (prologue: tiles 1 .. kRing-2)
     int c_next[kRing > 2 ? kRing - 2 : 1] = {0};
-    issue(0, 0);
+    if (SPLIT) {
+        if (wave < tiles) issue_own(wave);
+    } else {
+        issue(0, 0);
 #pragma unroll
-    for (int d = 0; d < kRing - 2; ++d) c_next[d] = d + 1 < tiles ? issue(d + 1, d + 1) : 0;
+        for (int d = 0; d < kRing - 2; ++d) c_next[d] = d + 1 < tiles ? issue(d + 1, d + 1) : 0;
+    }
 
     // ---- kStep: this head's slice of the group's 64 rows of x (two 16-byte units per thread) is requested
     // now and stored to the packed buffer after the first tile; head 0 also records the source rows
@@ -415,7 +461,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int j = m0 + 32 * i + (tid >> 3);
-            if (j < n)
+            if ((!SPLIT || 32 * i + (tid >> 3) < kBM) && j < n)
                 x_raw[i] = reinterpret_cast<const uint4*>(step.x + (pad0 + idx_lds[j]) * tok + head_off)[tid & 7];
         }
         if (h == 0 && tid < kBM && m0 + tid < n && (int64_t)s + m0 + tid < step.cap_rows)
@@ -423,7 +469,6 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
 
     // ---- Q: this lane's query row, head-dim elements 16g .. 16g+15 (zeros past the sequence end)
-    const int q_row = m0 + wave * 16 + col;
     uint4 q_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
     if (q_row < n) {
         const uint4* src = reinterpret_cast<const uint4*>(q + row_of(q_row) * tok + head_off + 16 * g);
@@ -452,6 +497,78 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     f32x4 o_acc[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) o_acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // one tile (in LDS at tile0) against this wavefront's queries
+    auto compute_tile = [&](int t, uint32_t tile0) {
+        const int rem = n - t * kBN;
+        const uint32_t k_a0 = tile0 + k_rel0, k_a1 = tile0 + (k_rel0 ^ 16u);
+        const uint32_t v_a0 = tile0 + v_rel0, v_a1 = tile0 + (v_rel0 ^ 16u);
+        if (rem >= kBN) {
+            tile_update<In, 4, false>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc);
+        } else {
+            switch ((rem + 15) >> 4) {
+                case 1: tile_update<In, 1, true>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                case 2: tile_update<In, 2, true>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                case 3: tile_update<In, 3, true>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                default: tile_update<In, 4, true>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+            }
+        }
+    };
+    // kStep: the x rows requested above go to the packed buffer
+    auto store_packed_rows = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = m0 + 32 * i + (tid >> 3);
+            if ((!SPLIT || 32 * i + (tid >> 3) < kBM) && j < n && (int64_t)s + j < step.cap_rows)
+                reinterpret_cast<uint4*>(step.packed + ((int64_t)s + j) * tok + head_off)[tid & 7] = x_raw[i];
+        }
+    };
+    if (SPLIT) {
+        // ---- this wavefront's tiles wave, wave + 4, ...: its own slot, its own loads, no barrier
+        const uint32_t tile0 = ring0 + wave * 2 * kTileBytes;
+        for (int t = wave; t < tiles; t += WAVES) {
+            wait_vm<0>();                   // the tile has landed (the loads were this wavefront's own)
+            compute_tile(t, tile0);         // its results depend on every LDS read of the tile: the slot is free after it
+            if (t + WAVES < tiles) issue_own(t + WAVES);
+        }
+        if (MODE == kStep) store_packed_rows();
+        // ---- merge the four partial results: part[j][lane], j = 0: running maximum, 1: row sum, 2 + 4dt + r: accumulators
+        float* const part = reinterpret_cast<float*>(ring) + wave * (2 * kTileBytes / 4);
+        part[lane] = m_run;
+        part[kWaveSize + lane] = l_acc[0];
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[(2 + 4 * dt + r) * kWaveSize + lane] = o_acc[dt][r];
+        __syncthreads();                    // (a wavefront without tiles contributes maximum -inf, sums 0)
+        if (q_row < n) {
+            const bool row_fits = MODE != kStep || (int64_t)s + q_row < step.cap_rows;
+            const float* const all = reinterpret_cast<const float*>(ring);
+            float m_w[WAVES], m_all = -INFINITY;
+#pragma unroll
+            for (int w2 = 0; w2 < WAVES; ++w2) {
+                m_w[w2] = all[w2 * (2 * kTileBytes / 4) + lane];
+                m_all = fmaxf(m_all, m_w[w2]);  // finite: wavefront 0 always has tile 0
+            }
+            float l_all = 0.f, o4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w2 = 0; w2 < WAVES; ++w2) {
+                const float f = __builtin_amdgcn_exp2f(m_w[w2] - m_all);
+                const float* pw = all + w2 * (2 * kTileBytes / 4);
+                l_all = __builtin_fmaf(f, pw[kWaveSize + lane], l_all);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o4[r] = __builtin_fmaf(f, pw[(2 + 4 * wave + r) * kWaveSize + lane], o4[r]);
+            }
+            const float inv = 1.0f / l_all;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o4[r] *= inv;
+            // this wavefront finishes head-dim elements 16g + 4*wave .. +3 of the lane's query
+            if (row_fits) store4(o + row_of(q_row) * tok_o + head_off + 16 * g + 4 * wave, o4);
+            if (MODE == kStep)
+                store4(reinterpret_cast<OutT*>(step.out) + (pad0 + idx_lds[q_row]) * tok_o + head_off + 16 * g + 4 * wave, o4);
+        }
+        return;
+    }
 
     int slot = 0;                                              // ring slot of tile t
     for (int t = 0; t < tiles; ++t) {
@@ -519,13 +636,17 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
                         const StepArgs& step, hipStream_t stream) {
     constexpr int kWaves = kAttnWaves;                         // 16 query rows each
     constexpr int kGroup = 512;                                // pairs per dispatch batch
-    const int q_tiles = (max_seqlen + 16 * kWaves - 1) / (16 * kWaves);
     const int pairs = B * H;
+    // Small launches (at most kSplitMaxGroups 64-row q-tiles, sequences that may span several K/V tiles) leave
+    // most CUs idle and are a chain of latencies: they take 16-row work-groups whose wavefronts split the keys.
+    const bool split = max_seqlen > kBN && (int64_t)pairs * ((max_seqlen + 16 * kWaves - 1) / (16 * kWaves)) <= kSplitMaxGroups;
+    const int tile_rows = split ? 16 : 16 * kWaves;
+    const int q_tiles = (max_seqlen + tile_rows - 1) / tile_rows;
     const int pairs8 = (pairs + kXcds - 1) / kXcds * kXcds;
     const int group = pairs8 < kGroup ? pairs8 : kGroup;
     const int batches = (pairs + group - 1) / group;
-    const hipError_t err = launch_kernel((attn_kernel<In, OutT, MODE>), dim3(batches * q_tiles * group),
-                       dim3(kAttnThreads), stream,
+    const hipError_t err = launch_kernel(split ? attn_kernel<In, OutT, MODE, true> : attn_kernel<In, OutT, MODE, false>,
+                       dim3(batches * q_tiles * group), dim3(kAttnThreads), stream,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                        static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, keep, n_tok,
                        fill_mode, H, in_tok, out_tok, pairs, q_tiles, group, fabsf(scale) * kLog2e,

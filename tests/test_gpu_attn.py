@@ -215,19 +215,27 @@ def _checked(lengths, bound, H=2, seed=606):
     return o.cpu(), int(flags.item()), (q, k, v, cu)
 
 
+def _oracle_rows(q, k, v, cu):
+    return oracle.attn(wl.to_words(q), wl.to_words(k), wl.to_words(v), cu, 0.125, "f16", threads=8)
+
+
 def test_checked_attention_reports_a_bound_that_is_too_small():
-    """max_seqlen below some n_i: the flag bit is set on the device, every kernel exits normally, the rows the
-    grid does cover equal ragged_attn's bit for bit, and the rows it does not cover stay untouched."""
+    """max_seqlen below some n_i: the flag bit is set on the device, every kernel exits normally, every row at a
+    position below the bound is computed (oracle bar), rows of the offending image at or past the bound rounded
+    up to the 64-row tile stay untouched, and the other images are complete."""
     from paper_2604_15408_amd import binding
     lengths = [30, 150, 10, 64]
     raw, flags, (q, k, v, cu) = _checked(lengths, bound=64)         # image 1 has 150 > 64 tokens
     assert flags & binding.FLAG_SEQLEN_EXCEEDED
-    _, full = hp.gpu_attn(q, k, v, cu, 150, 0.125)
-    a, b = raw.view(torch.int16), full.view(torch.int16)
+    want = _oracle_rows(q, k, v, cu)
+    got = raw.to(torch.float64).numpy()
     covered = np.ones(int(cu[-1]), dtype=bool)
     covered[cu[1] + 64: cu[2]] = False                               # query rows 64.. of image 1 are lost
-    assert torch.equal(a[covered], b[covered])
+    assert np.max(np.abs(got[covered] - want[covered])) <= TOL
     assert bool((raw[~covered] == 77.0).all())
+    # the same call without the flag word gives the same bits
+    _, plain = hp.gpu_attn(q, k, v, cu, 64, 0.125)
+    assert torch.equal(raw.view(torch.int16), plain.view(torch.int16))
 
 
 def test_checked_attention_keeps_the_flag_clear_when_the_bound_holds():
@@ -237,11 +245,45 @@ def test_checked_attention_keeps_the_flag_clear_when_the_bound_holds():
         assert flags == 0
         _, full = hp.gpu_attn(q, k, v, cu, bound, 0.125)
         assert torch.equal(raw.view(torch.int16), full.view(torch.int16))
-    # a bound between n_i and the next multiple of 64 loses nothing but is still reported: 150 > 140
+        assert np.max(np.abs(raw.to(torch.float64).numpy() - _oracle_rows(q, k, v, cu))) <= TOL
+    # a bound just below n_i is reported too; rows below the bound are all there, rows at or past it may be missing
     raw, flags, (q, k, v, cu) = _checked(lengths, bound=140)
     assert flags == 1
-    _, full = hp.gpu_attn(q, k, v, cu, 150, 0.125)
-    assert torch.equal(raw.view(torch.int16), full.view(torch.int16))
+    want = _oracle_rows(q, k, v, cu)
+    got = raw.to(torch.float64).numpy()
+    below = np.ones(int(cu[-1]), dtype=bool)
+    below[cu[1] + 140: cu[2]] = False
+    assert np.max(np.abs(got[below] - want[below])) <= TOL
+    tail = raw[cu[1] + 140: cu[2]]
+    for row, ref in zip(tail.to(torch.float64).numpy(), want[cu[1] + 140: cu[2]]):
+        assert bool((row == 77.0).all()) or np.max(np.abs(row - ref)) <= TOL      # untouched, or computed whole
+
+
+def test_small_launches_split_the_keys_over_the_wavefronts():
+    """Launches of few work-groups take the key-split form (16-query work-groups, partial results merged through
+    LDS); large ones the 64-query form.  The same sequences through both: each within the oracle bar, single-tile
+    sequences bit-identical (nothing to merge), longer ones equal within rounding."""
+    lengths = [30, 150, 10, 64, 197, 1, 65, 256, 257, 300]
+    cu = hp.cu_from_lengths(lengths)
+    q, k, v = _qkv(int(cu[-1]), 2, "f16", 611)
+    want = _oracle_rows(q, k, v, cu)
+    small, raw_small = hp.gpu_attn(q, k, v, cu, 300, 0.125)          # 20 pairs x 5 q-tiles: key-split form
+    # the same rows inside a batch large enough for the 64-query form: 60 images, 120 pairs x 5 q-tiles
+    reps = 6
+    cu_big = hp.cu_from_lengths(lengths * reps)
+    qb, kb, vb = (t.repeat(reps, 1, 1).contiguous() for t in (q, k, v))
+    big, raw_big = hp.gpu_attn(qb, kb, vb, cu_big, 300, 0.125)
+    T = int(cu[-1])
+    assert np.max(np.abs(small - want)) <= TOL and np.max(np.abs(big[:T] - want)) <= TOL
+    for r in range(1, reps):                                        # copies of a sequence inside one launch: same bits
+        assert torch.equal(raw_big[:T].view(torch.int16), raw_big[r * T:(r + 1) * T].view(torch.int16))
+    a, b = raw_small.view(torch.int16), raw_big[:T].view(torch.int16)
+    for i, n in enumerate(lengths):
+        rows = slice(int(cu[i]), int(cu[i + 1]))
+        if n <= 64:
+            assert torch.equal(a[rows], b[rows])
+        else:
+            assert np.max(np.abs(small[rows] - big[rows])) <= 1e-3
 
 
 def test_permutation_equivariance_within_tolerance():
