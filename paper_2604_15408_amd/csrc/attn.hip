@@ -179,12 +179,15 @@ __device__ __forceinline__ void tile_update(uint32_t k_a0, uint32_t k_a1, uint32
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             t_max = fmaxf(t_max, (!MASK || kt < NT - 1 || r < last_valid) ? st[kt][r] : -INFINITY);
-    t_max = quad_max(t_max) * scale_log2e;                      // finite: the tile has a valid key
     // Lazy rescaling: the reference maximum m_run only moves when some query's tile maximum exceeds
     // it by more than 2^kLazyLog2 (always on the first tile, where m_run = -inf).  Until then
     // probabilities may reach 2^kLazyLog2 instead of 1 -- harmless in fp16/bf16/fp32 -- and the
     // accumulators need no per-tile multiply.  The result is the same softmax: m_run cancels.
-    if (__builtin_amdgcn_ballot_w64(t_max > m_run + kLazyLog2) != 0) {   // wavefront-uniform
+    // The test is made on each lane's own maximum (a query's four lanes share m_run, so some lane
+    // passes it exactly when the query's maximum does); the cross-lane reduction is only paid when
+    // the reference really moves.
+    if (__builtin_amdgcn_ballot_w64(t_max * scale_log2e > m_run + kLazyLog2) != 0) {   // wavefront-uniform
+        t_max = quad_max(t_max) * scale_log2e;                  // finite: the tile has a valid key
         const float m_new = fmaxf(m_run, t_max);
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         m_run = m_new;
