@@ -56,6 +56,11 @@ typedef enum {
  *   cu_seqlens [B + 1]     out: cu[0] = 0, cu[i+1] = cu[i] + n_i
  *   gather_idx [cap_rows]  out: gather_idx[r] = flat source row i*N + t of packed row r
  *
+ * Cost note: every work-group recounts the keep bytes in front of its chunk (no grid-wide scan, no second
+ * launch, no workspace), i.e. O(B*N) mask bytes per work-group from L2.  That is free at ViT batch sizes (B*N up to
+ * a few 10^4) and grows quadratically with the batch: around B*N = 10^6 the recount costs as much as the copy.
+ * ragged_repack and ragged_pack_attn_unpack count the same way.
+ *
  * cap_rows is the row capacity of `packed` and `gather_idx`.  B*N always suffices.  Rows whose
  * destination would be >= cap_rows are not written (cu_seqlens still holds the true counts, so the
  * caller can detect the overflow from cu_seqlens[B] afterwards).  Rows >= T are left untouched.

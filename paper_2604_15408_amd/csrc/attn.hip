@@ -535,6 +535,21 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             if (t + WAVES < tiles) issue_own(t + WAVES);
         }
         if (MODE == kStep) store_packed_rows();
+        if (tiles == 1) {                   // a single tile: wavefront 0 holds the whole result, nothing to merge
+            if (wave == 0 && q_row < n) {
+                const bool row_fits = MODE != kStep || (int64_t)s + q_row < step.cap_rows;
+                const float inv = 1.0f / l_acc[0];
+                float out16[16];
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) out16[4 * dt + r] = o_acc[dt][r] * inv;
+                if (row_fits) store16(o + row_of(q_row) * tok_o + head_off + 16 * g, out16);
+                if (MODE == kStep)
+                    store16(reinterpret_cast<OutT*>(step.out) + (pad0 + idx_lds[q_row]) * tok_o + head_off + 16 * g, out16);
+            }
+            return;
+        }
         // ---- merge the four partial results: part[j][lane], j = 0: running maximum, 1: row sum, 2 + 4dt + r: accumulators
         float* const part = reinterpret_cast<float*>(ring) + wave * (2 * kTileBytes / 4);
         part[lane] = m_run;
