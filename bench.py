@@ -89,6 +89,9 @@ def other_configs(torch, steps: int):
         "B": layers[0].B, "T_per_layer": [w.T for w in layers],
         "pack_attn_unpack_per_layer": pipeline_point(torch, Pipeline(layers, fill_mode=1), 36, alg),
     }
+    fused_alg = sum(algorithmic(w, 1)["pack_attn_unpack"]["bytes"] for w in layers)
+    out["pipeline_12_layers"]["one_launch_per_layer"] = pipeline_point(torch, Pipeline(layers, fill_mode=1, one_launch=True),
+                                                                       12, fused_alg)
     stay = StayPackedPipeline(layers)
     out["pipeline_12_layers"]["stay_packed"] = pipeline_point(torch, stay, stay.launches)
     return out

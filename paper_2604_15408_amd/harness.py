@@ -294,12 +294,14 @@ class Pipeline:
     pack(X_l, mask_l) -> ragged_attn(Q_l, K_l, V_l; cu_seqlens from pack) -> unpack(O_l) -> X_{l+1}.
     There are no projection weights, so Q/K/V of every layer are seeded N(0,1) tensors of that
     layer's packed length; pack's row output is produced (and parity-checked in the tests) but feeds
-    nothing downstream.  All 36 launches use upper-bound grids, so the loop is graph-capturable."""
+    nothing downstream.  All 36 launches use upper-bound grids, so the loop is graph-capturable.
+    one_launch=True issues every layer as ONE ragged_pack_attn_unpack launch instead (12 kernels, the same
+    outputs bit for bit); its Q/K/V/O buffers then hold B*N rows, as that entry point asks."""
 
-    def __init__(self, layers, fill_mode: int = 1):
+    def __init__(self, layers, fill_mode: int = 1, one_launch: bool = False):
         import torch
         from paper_2604_15408_amd import binding
-        self.torch, self.b, self.layers, self.fill_mode = torch, binding, layers, fill_mode
+        self.torch, self.b, self.layers, self.fill_mode, self.one_launch = torch, binding, layers, fill_mode, one_launch
         dev = "cuda:0"
         w0 = layers[0]
         B, N, C, H, D = w0.B, w0.N, w0.C, w0.H, w0.D
@@ -309,14 +311,25 @@ class Pipeline:
         self.packed = torch.zeros(B * N, C, dtype=torch.float16, device=dev)
         self.cu = [torch.zeros(B + 1, dtype=torch.int32, device=dev) for _ in layers]
         self.gidx = [torch.zeros(B * N, dtype=torch.int32, device=dev) for _ in layers]
-        self.qkv = [tuple(t.to(dev) for t in w.qkv(max(w.T, 1))) for w in layers]
-        self.o = [torch.zeros(max(w.T, 1), H, D, dtype=torch.float16, device=dev) for w in layers]
+        rows = lambda w: B * N if one_launch else max(w.T, 1)
+        self.qkv = []
+        for w in layers:
+            bufs = tuple(torch.zeros(rows(w), H, D, dtype=torch.float16, device=dev) for _ in range(3))
+            for dst, src in zip(bufs, w.qkv(max(w.T, 1))):
+                dst[: src.shape[0]] = src.to(dev)              # rows past T are never read
+            self.qkv.append(bufs)
+        self.o = [torch.zeros(rows(w), H, D, dtype=torch.float16, device=dev) for w in layers]
+        self.launches = (1 if one_launch else 3) * len(layers)
         torch.cuda.synchronize()
 
     def run(self):
         b = self.b
         for l, w in enumerate(self.layers):
             q, k, v = self.qkv[l]
+            if self.one_launch:
+                b.ragged_pack_attn_unpack(self.x[l], self.keep[l], q, k, v, self.packed, self.cu[l], self.gidx[l],
+                                          self.o[l], self.x[l + 1], w.scale, self.fill_mode)
+                continue
             b.ragged_pack(self.x[l], self.keep[l], self.packed, self.cu[l], self.gidx[l])
             b.ragged_attn(q, k, v, self.o[l], self.cu[l], w.N, w.scale)
             b.ragged_unpack(self.o[l].view(-1, w.C), self.keep[l], self.cu[l], self.gidx[l],

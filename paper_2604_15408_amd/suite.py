@@ -113,17 +113,17 @@ def library_padded_sdpa_us(torch, w):
         return None
 
 
-def pipeline_case(torch):
+def pipeline_case(torch, one_launch: bool = False):
     layers = wl.pipeline()
-    pipe = Pipeline(layers, fill_mode=1)
+    pipe = Pipeline(layers, fill_mode=1, one_launch=one_launch)
     pipe.run()
     torch.cuda.synchronize()
     g = capture(torch, pipe.run)
     us_graph = event_time_us(torch, g.replay, iters=30)[0]
     wall_graph = wall_steps(torch, g.replay, 100) * 1e6
     wall_eager = wall_steps(torch, pipe.run, 100) * 1e6
-    return {"case": "pipeline_12_layers", "B": layers[0].B, "N": layers[0].N,
-            "T_per_layer": [w.T for w in layers], "tokens": pipe.tokens, "kernels_in_graph": 36,
+    return {"case": "pipeline_12_layers" + ("_one_launch_per_layer" if one_launch else ""), "B": layers[0].B, "N": layers[0].N,
+            "T_per_layer": [w.T for w in layers], "tokens": pipe.tokens, "kernels_in_graph": pipe.launches,
             "graph_gpu_us": us_graph, "graph_wall_us": wall_graph, "eager_wall_us": wall_eager,
             "tokens_per_s": pipe.tokens / (wall_graph * 1e-6)}
 
@@ -340,6 +340,7 @@ def main():
             emit(case(torch, wl.serving_384(B), "serving_384"))
     if want("pipeline"):
         emit(pipeline_case(torch))
+        emit(pipeline_case(torch, one_launch=True))
         emit(stay_packed_case(torch))
     if want("late_blocks"):
         emit(late_blocks_case(torch, wl.deit_b_pruned(0.2, 32, "f16", 1001), "late_blocks_headline", keep_prob=0.2))

@@ -110,6 +110,28 @@ def test_full_size_twelve_layer_graph_against_the_oracle():
     assert np.array_equal(wl.to_words(pipe.x[-1].cpu()), want_x)
 
 
+def test_one_launch_per_layer_loop_equals_the_three_launch_loop():
+    """The 12 layers as 12 ragged_pack_attn_unpack launches in one graph: every cu_seqlens, every attention row and
+    the final padded tensor equal the 36-kernel loop's bit for bit (which the tests above hold against the oracle)."""
+    layers = _small_pipeline()
+    ref = Pipeline(layers, fill_mode=1)
+    ref.run()
+    one = Pipeline(layers, fill_mode=1, one_launch=True)
+    one.run()
+    g = capture(torch, one.run)
+    for rep in range(2):
+        for t in one.x[1:] + one.o:
+            t.fill_(9.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for l, w in enumerate(layers):
+            assert torch.equal(one.cu[l], ref.cu[l])
+            assert torch.equal(one.gidx[l][: w.T], ref.gidx[l][: w.T])
+            assert torch.equal(one.o[l][: w.T].view(torch.int16), ref.o[l][: w.T].view(torch.int16))
+            assert torch.equal(one.x[l + 1].view(torch.int16), ref.x[l + 1].view(torch.int16))
+
+
 def test_stay_packed_loop_matches_the_unpack_pack_loop_and_oracle():
     """Pack once, stay packed (strided attention, re-pack at the pruning layers, CLS read at the end):
     same lengths and attention rows as the loop that goes through the padded tensor every layer."""
