@@ -1,7 +1,8 @@
 // Bidirectional multi-head attention over a packed ragged buffer (Section 4.2, Algorithm 1), for
 // gfx950: one launch, one work-group per (image, head, 64-query tile), K/V tiles streamed through a
 // ring of LDS buffers by direct global->LDS loads, MFMA 16x16x32 for both contractions with fp32
-// accumulation, fp32 online softmax.
+// accumulation, fp32 online softmax.  Small launches take a second form of the same kernel (SPLIT:
+// 16-query work-groups whose wavefronts split the keys; described at the kernel).
 //
 // Orientation.  Each wavefront owns 16 queries and computes the TRANSPOSED score tile
 // S^T = K Q^T (keys x queries).  In the MFMA result layout a lane then holds, for ONE query
@@ -51,7 +52,7 @@ constexpr int kBN = 64;                 // keys per K/V tile
 // (3, 4) lose resident wavefronts and gain nothing, eight-wavefront groups with rings of 2..4 tie
 // on dense batches and lose on short sequences.
 constexpr int kRing = 2;                // K/V tiles resident in LDS per work-group (2..4)
-constexpr int kAttnWaves = 4;           // wavefronts (16 queries each) per work-group: 4 or 8
+constexpr int kAttnWaves = 4;           // wavefronts per work-group: 4 or 8 (the key-split and single-launch forms need 4)
 constexpr int kAttnThreads = kWaveSize * kAttnWaves;
 constexpr int kAttnOcc = kAttnWaves == 8 ? 2 : (kRing == 2 ? 4 : (kRing == 3 ? 3 : 2));  // work-groups per CU aimed at
 constexpr int kTileBytes = kBN * kHeadDim * 2;   // one K or one V tile: 8 KB
@@ -287,6 +288,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     constexpr bool LIST = MODE != kPacked;                     // the kept list is built from the mask
     static_assert(MODE != kStep || (kAttnThreads == kBlockThreads && kAttnWaves == 4),
                   "the mask prefix count and the x copy of kStep assume 256 threads and 64-row q-tiles");
+    static_assert(!SPLIT || kAttnWaves == 4, "the merge of the key-split form gives each of four wavefronts four elements");
     constexpr int WAVES = kAttnWaves;
     constexpr int kI = 8 / WAVES;                              // load instructions per wavefront per K (or V) tile
     constexpr int kPer = 2 * kI;                               // ... per K+V tile
