@@ -86,6 +86,9 @@ int ragged_pack(const void* x, const uint8_t* keep, int B, int N, int C, ragged_
  *   scale                  finite fp32 softmax scale (the paper uses 1/sqrt(D))
  *
  * Supported: D = 64; (in_dt, out_dt) in {F16->F16, F16->F32, BF16->BF16, BF16->F32}.
+ * Limits of the launch (RAGGED_ERR_SHAPE beyond them; the same for every attention entry point, with N in
+ * place of max_seqlen where the call has no bound): max_seqlen <= 64 * 65535, B * H <= 512 * 65535, and
+ * ceil(B*H / 512) * 512 * ceil(max_seqlen / 64) < 2^31 work-groups.
  * Contractions run on MFMA with fp32 accumulation; the softmax runs in fp32.
  * Images with n_i = 0 produce no rows.  Results are bit-reproducible from run to run with the same arguments.
  * The launch shape follows B, H and max_seqlen (small launches split the keys of a sequence over the wavefronts
@@ -107,8 +110,8 @@ int ragged_attn(const void* q, const void* k, const void* v, void* o,
  * q = base, k = base + H*D, v = base + 2*H*D with in_tok_stride = 3*H*D attends on it in place,
  * without three de-interleaving copies.  ragged_attn is this call with both strides = H*D.
  *
- * Strides are in elements of the respective dtype, must be >= H*D (in_tok_stride also <= 2^23,
- * else RAGGED_ERR_SHAPE), and every token row must start
+ * Strides are in elements of the respective dtype, must be >= H*D (in_tok_stride also <= 2^23 and
+ * out_tok_stride < 2^31, else RAGGED_ERR_SHAPE), and every token row must start
  * on a 16-byte boundary (in_tok_stride a multiple of 8; out_tok_stride a multiple of 8 for 16-bit
  * outputs, of 4 for F32).  Everything else as for ragged_attn; outputs are bit-identical to
  * ragged_attn on contiguous copies of the same rows.

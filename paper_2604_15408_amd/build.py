@@ -21,6 +21,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # never let the compiler form packed-fp32 VALU ops (unreliable on this target)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the first 14 dwords of a kernel's arguments arrive in scalar registers with the wavefront instead of
+    # being fetched by its first instructions (the kernels order their parameters by first use)
+    "-mllvm", "-amdgpu-kernarg-preload-count=14",
     f"-I{ROOT / 'include'}", f"-I{CSRC}",
 ]
 

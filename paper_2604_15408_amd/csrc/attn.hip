@@ -62,6 +62,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazyLog2 = 8.0f;       // probabilities stay below 2^8 between rescales
 constexpr int kSplitMaxGroups = 256;    // launches of at most this many 64-row q-tiles split the keys over the wavefronts
 constexpr int kMaxGatherTokens = 1536;  // tokens per image the gather-on-load variant can index in LDS
+constexpr int kMaxGridYZ = 65535;       // HIP's limit on the second and third grid dimension
 
 // O^T += V^T P^T for one 32-key block: p[0..7] are this lane's probabilities (fp32).  The row sums
 // of P ride along on the matrix core: with an all-ones A operand every row of the result holds
@@ -260,9 +261,10 @@ __device__ __forceinline__ void tile_any(int rem, uint32_t tile0, uint32_t k_rel
     }
 }
 
-// Work-group index -> (q-tile, image-head pair).  Pairs are taken in batches of `group` (a multiple
-// of 8); inside a batch the order is q-tile-major:  bid = (batch*q_tiles + m_tile)*group + slot,
-// pair = batch*group + slot.
+// Work-group -> (q-tile, image-head pair).  Pairs are taken in batches of `group` (a multiple of 8);
+// inside a batch the order is q-tile-major: the grid is (group, q_tiles, batches), dispatched
+// x-fastest, so work-group (slot, m_tile, batch) is number (batch*q_tiles + m_tile)*group + slot in
+// dispatch order and handles pair = batch*group + slot.
 //   * The hardware deals consecutive work-groups round-robin to the 8 XCDs (each with its own L2),
 //     and group is a multiple of 8, so every q-tile of a pair lands on XCD slot%8 and re-reads that
 //     pair's K/V through one L2.
@@ -312,11 +314,16 @@ struct StepArgs {
 //   A sequence of up to 256 tokens then costs one tile time plus the merge instead of up to four.
 template <typename In, typename OutT, int MODE, bool SPLIT>
 __global__ __launch_bounds__(kAttnThreads, SPLIT ? 2 : (kAttnOcc < 1 ? 1 : kAttnOcc))
-void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-                 const uint16_t* __restrict__ v, OutT* __restrict__ o,
-                 const int32_t* __restrict__ cu_seqlens, const uint8_t* __restrict__ keep, int n_tok,
-                 int fill_mode, int H, int64_t tok, int64_t tok_o, int pairs, int q_tiles, int group,
-                 float scale_log2e, int negate_q, StepArgs step) {
+void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H, uint32_t h_magic, int pairs,
+                 int group, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int tok32,
+                 int tok_o32, const uint16_t* __restrict__ q, OutT* __restrict__ o, float scale_log2e,
+                 int negate_q, StepArgs step) {
+    // The parameters are ordered by when the kernel needs them: the first 14 dwords (up to tok_o32) are
+    // delivered in scalar registers with the wavefront (kernel-argument preload), the rest is fetched while
+    // the first memory round trip is under way.
+    const int32_t* const cu_seqlens = static_cast<const int32_t*>(index);      // MODE kPacked
+    const uint8_t* const keep = static_cast<const uint8_t*>(index);            // the modes that read a keep mask
+    const int64_t tok = tok32, tok_o = tok_o32;
     typedef typename In::vec8 vec8;
     constexpr bool GATHER = MODE == kPadded;                   // q, k, v, o rows addressed through the kept list
     constexpr bool LIST = MODE != kPacked;                     // the kept list is built from the mask
@@ -329,15 +336,14 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     constexpr int kBM = SPLIT ? 16 : 16 * WAVES;               // queries per work-group
     __shared__ __attribute__((aligned(1024))) uint4 ring[(SPLIT ? WAVES : kRing) * 2 * kTileBytes / 16];   // [slot][K|V]
 
-    // bid = (batch * q_tiles + m_tile) * group + slot ; pair = batch * group + slot
-    const int per_batch = q_tiles * group;
-    const int batch = blockIdx.x / per_batch;
-    const int in_batch = blockIdx.x - batch * per_batch;
-    const int m_tile = in_batch / group;
-    const int pair = batch * group + (in_batch - m_tile * group);
+    // grid (group, q_tiles, batches): work-groups are dispatched x-fastest, i.e. in the order
+    // (batch * q_tiles + m_tile) * group + slot of the mapping described above, with no division to undo it
+    const int m_tile = blockIdx.y;
+    const int pair = blockIdx.z * group + blockIdx.x;
     if (pair >= pairs) return;
-    const int h = pair % H;
-    const int img = pair / H;
+    uint32_t img_u, h_u;
+    divmod((uint32_t)pair, (uint32_t)H, h_magic, img_u, h_u);
+    const int img = (int)img_u, h = (int)h_u;
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -350,6 +356,7 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     __shared__ uint16_t idx_lds[LIST ? kMaxGatherTokens : 1];      // kept token positions, ascending
     constexpr int kRounds = kMaxGatherTokens / kAttnThreads;       // mask bytes per thread: all requested up front
     __shared__ int wave_cnt[LIST ? kRounds * WAVES : 1];
+    __shared__ uint64_t keep_bits[LIST ? kRounds * WAVES : 1];     // fill_mode 1: keep bits of tokens 64e .. 64e+63 in entry e
     __shared__ int lds4[4];
     int s, n;
     if (LIST) {
@@ -359,33 +366,23 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         s = img * n_tok;
         PrefixLoads before_image;
         if (MODE == kStep) before_image = prefix_issue(keep, img * n_tok);   // requested with the image's own mask
-        bool pre[kRounds];
+        // the image's own mask bytes: every round requested before any is looked at (clamped loads, see
+        // load_byte_clamped), so the mask and the prefix words cost ONE memory round trip together
+        uint8_t raw[kRounds];
 #pragma unroll
-        for (int j = 0; j < kRounds; ++j) {
-            const int t = j * kThreads + tid;
-            pre[j] = t < n_tok && mask[t] != 0;
-        }
-        if (fill_mode == 1 && m_tile == 0) {                   // zero this head's slice of dropped rows
-            if (MODE == kStep) {
-                for (int t = tid / 8; t < n_tok; t += kThreads / 8)
-                    if (mask[t] == 0)
-                        reinterpret_cast<uint4*>(step.out + (int64_t)(s + t) * tok_o + head_off)[tid % 8] =
-                            make_uint4(0, 0, 0, 0);
-            } else {
-                constexpr int kChunks = kHeadDim * (int)sizeof(OutT) / 16;
-                for (int t = tid / kChunks; t < n_tok; t += kThreads / kChunks)
-                    if (mask[t] == 0)
-                        reinterpret_cast<uint4*>(o + (s + t) * tok_o + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
-            }
-        }
+        for (int j = 0; j < kRounds; ++j) raw[j] = load_byte_clamped(mask, j * kThreads + tid, n_tok);
         // Count first (one barrier): a group learns the image's length n before anything else is built, and
         // the groups of the upper-bound grid that have no rows leave here.
+        const bool zero_fill = fill_mode == 1 && m_tile == 0;  // this group zeroes the head's slice of the dropped rows
         uint64_t bits[kRounds];
 #pragma unroll
         for (int j = 0; j < kRounds; ++j)
-            if (j * kThreads < n_tok) {                        // group-uniform
-                bits[j] = __ballot(pre[j]);
-                if (lane == 0) wave_cnt[j * WAVES + wave] = __popcll(bits[j]);
+            if (j * kThreads < n_tok) {
+                bits[j] = __ballot(j * kThreads + tid < n_tok && raw[j] != 0);
+                if (lane == 0) {
+                    wave_cnt[j * WAVES + wave] = __popcll(bits[j]);
+                    if (zero_fill) keep_bits[j * WAVES + wave] = bits[j];
+                }
             }
         __syncthreads();
         n = 0;
@@ -401,12 +398,25 @@ void attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     n += c;
                 }
             }
+        if (zero_fill) {                                       // token t's keep bit: entry t / 64, bit t % 64
+            if (MODE == kStep) {
+                for (int t = tid / 8; t < n_tok; t += kThreads / 8)
+                    if (((keep_bits[t >> 6] >> (t & 63)) & 1ull) == 0)
+                        reinterpret_cast<uint4*>(step.out + (int64_t)(s + t) * tok_o + head_off)[tid % 8] =
+                            make_uint4(0, 0, 0, 0);
+            } else {
+                constexpr int kChunks = kHeadDim * (int)sizeof(OutT) / 16;
+                for (int t = tid / kChunks; t < n_tok; t += kThreads / kChunks)
+                    if (((keep_bits[t >> 6] >> (t & 63)) & 1ull) == 0)
+                        reinterpret_cast<uint4*>(o + (s + t) * tok_o + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
+            }
+        }
         n = __builtin_amdgcn_readfirstlane(n);
         // a group with no rows that does not write cu_seqlens either is done (whole group, before any further barrier)
         if (m0 >= n && !(MODE == kStep && h == 0 && m_tile == 0)) return;
 #pragma unroll
         for (int j = 0; j < kRounds; ++j)
-            if (j * kThreads < n_tok && pre[j])
+            if (j * kThreads < n_tok && ((bits[j] >> lane) & 1ull) != 0)
                 idx_lds[before[j] + __popcll(bits[j] & ((1ull << lane) - 1ull))] = (uint16_t)(j * kThreads + tid);
         if (MODE == kStep) {
             s = prefix_finish(keep, before_image, lds4);       // kept tokens of the images before this one; its
@@ -728,12 +738,14 @@ hipError_t launch_typed(const void* q, const void* k, const void* v, void* o,
     const int pairs8 = (pairs + kXcds - 1) / kXcds * kXcds;
     const int group = pairs8 < kGroup ? pairs8 : kGroup;
     const int batches = (pairs + group - 1) / group;
+    if (q_tiles > kMaxGridYZ || batches > kMaxGridYZ || in_tok > INT32_MAX || out_tok > INT32_MAX)
+        return hipErrorInvalidValue;                            // (the C ABI layer has refused these already)
     const hipError_t err = launch_kernel(split ? attn_kernel<In, OutT, MODE, true> : attn_kernel<In, OutT, MODE, false>,
-                       dim3(batches * q_tiles * group), dim3(kAttnThreads), stream,
-                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
-                       static_cast<const uint16_t*>(v), static_cast<OutT*>(o), cu_seqlens, keep, n_tok,
-                       fill_mode, H, in_tok, out_tok, pairs, q_tiles, group, fabsf(scale) * kLog2e,
-                       scale < 0.f ? 1 : 0, step);
+                       dim3(group, q_tiles, batches), dim3(kAttnThreads), stream,
+                       MODE == kPacked ? static_cast<const void*>(cu_seqlens) : static_cast<const void*>(keep),
+                       n_tok, fill_mode, H, div_magic((uint32_t)H), pairs, group, static_cast<const uint16_t*>(k),
+                       static_cast<const uint16_t*>(v), (int)in_tok, (int)out_tok, static_cast<const uint16_t*>(q),
+                       static_cast<OutT*>(o), fabsf(scale) * kLog2e, scale < 0.f ? 1 : 0, step);
     return err;
 }
 

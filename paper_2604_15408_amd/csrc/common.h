@@ -25,6 +25,19 @@ inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block
     return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, stream);
 }
 
+// Division by a number the host knows, without the hardware's 40-instruction integer division: with
+// magic = floor((2^32 - 1) / d) the high half of n * magic is floor(n / d) or one less (the error
+// n * (2^32 - magic*d) / (d * 2^32) is below n / 2^32 < 1), so one correction step makes it exact for
+// every 32-bit n and every d >= 1.
+inline uint32_t div_magic(uint32_t d) { return 0xFFFFFFFFu / d; }
+__device__ __forceinline__ void divmod(uint32_t n, uint32_t d, uint32_t magic, uint32_t& quot, uint32_t& rem) {
+    uint32_t q = __umulhi(n, magic);
+    uint32_t r = n - q * d;
+    if (r >= d) { ++q; r -= d; }
+    quot = q;
+    rem = r;
+}
+
 // Host launchers (one kernel each).  All arguments have been validated by the C ABI layer.
 hipError_t launch_pack(const void* x, const uint8_t* keep, int B, int N, int C, void* packed,
                        int64_t cap_rows, int32_t* cu_seqlens, int32_t* gather_idx,

@@ -45,14 +45,27 @@ __device__ __forceinline__ int wave_sum(int v) {
 // other memory traffic between them: prefix_issue() starts the loads (first 16 KB of the range into
 // registers), prefix_finish() consumes them, handles any remainder, and reduces over the group.
 // Every thread of the 256-thread group must call both; every thread receives the total.  The bulk
-// is read as aligned 16-byte words; the unaligned head and the tail go byte by byte, so no byte
-// outside [0, len) is ever touched.
+// is read as aligned 16-byte words; the unaligned head and the tail go byte by byte.  No byte outside
+// [0, len) is touched, except that base[0] is read when len is 0: base must point at a readable byte
+// (every caller passes the start of a mask that is not empty).
+//
+// The byte loads are unconditional, with the index clamped into the range, and their values are only
+// looked at in prefix_finish().  A predicated byte load ("in range ? base[i] : 0") is compiled into
+// load, wait, compare inside the branch: every such load then costs a memory round trip of its own,
+// in front of whatever the caller wanted to have in flight together with the prefix.
 constexpr int kPrefixWords = 4;    // 16-byte words per thread kept in flight: 16 KB per pass of the group
+
+// A byte whose use can wait: base[min(i, len - 1)] (base[0] when len <= 0), never predicated.
+__device__ __forceinline__ uint8_t load_byte_clamped(const uint8_t* __restrict__ base, int i, int len) {
+    int j = i < len ? i : len - 1;
+    j = j > 0 ? j : 0;
+    return base[j];
+}
 
 struct PrefixLoads {
     uint4 w[kPrefixWords];   // words tid + 256*j of the aligned body (zero if absent)
-    uint8_t hb, tb;          // one head byte / one tail byte (zero if absent)
-    int head, body;
+    uint8_t hb, tb;          // a head byte / a tail byte: count only where tid < head / tail0 + tid < len
+    int head, body, len;
 };
 
 __device__ __forceinline__ PrefixLoads prefix_issue(const uint8_t* __restrict__ base, int len) {
@@ -62,13 +75,13 @@ __device__ __forceinline__ PrefixLoads prefix_issue(const uint8_t* __restrict__ 
     p.head = mis ? 16 - mis : 0;
     if (p.head > len) p.head = len;
     p.body = (len - p.head) >> 4;                             // whole 16-byte words
+    p.len = len;
     const uint4* words = reinterpret_cast<const uint4*>(base + p.head);
 #pragma unroll
     for (int j = 0; j < kPrefixWords; ++j)
         p.w[j] = tid + j * kBlockThreads < p.body ? words[tid + j * kBlockThreads] : make_uint4(0u, 0u, 0u, 0u);
-    p.hb = tid < p.head ? base[tid] : (uint8_t)0;
-    const int tail0 = p.head + (p.body << 4);
-    p.tb = tail0 + tid < len ? base[tail0 + tid] : (uint8_t)0;   // fewer than 16 tail bytes
+    p.hb = load_byte_clamped(base, tid, len);
+    p.tb = load_byte_clamped(base, p.head + (p.body << 4) + tid, len);   // fewer than 16 tail bytes
     return p;
 }
 
@@ -78,7 +91,8 @@ __device__ __forceinline__ int count_word(uint4 v) {
 
 __device__ inline int prefix_finish(const uint8_t* __restrict__ base, const PrefixLoads& p, int* lds4) {
     const int tid = threadIdx.x;
-    int count = (p.hb != 0) + (p.tb != 0);
+    const int tail0 = p.head + (p.body << 4);
+    int count = (tid < p.head && p.hb != 0) + (tail0 + tid < p.len && p.tb != 0);
 #pragma unroll
     for (int j = 0; j < kPrefixWords; ++j)
         if (j * kBlockThreads < p.body) count += count_word(p.w[j]);      // group-uniform: skip absent passes

@@ -27,10 +27,11 @@ template <bool EARLY>
 __global__ __launch_bounds__(kBlockThreads)
 void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, int N, int units,
                  uint4* __restrict__ packed, int64_t cap_rows, int32_t* __restrict__ cu_seqlens,
-                 int32_t* __restrict__ gather_idx, int chunk, int chunks_per_image) {
+                 int32_t* __restrict__ gather_idx, int chunk, int chunks_per_image, uint32_t cpi_magic) {
     __shared__ int lds4[4];
-    const int i = blockIdx.x / chunks_per_image;
-    const int c = blockIdx.x - i * chunks_per_image;
+    uint32_t i_u, c_u;
+    divmod(blockIdx.x, (uint32_t)chunks_per_image, cpi_magic, i_u, c_u);
+    const int i = (int)i_u, c = (int)c_u;
     const int t0 = c * chunk;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
@@ -39,12 +40,14 @@ void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, 
     // Three dependent fabric round trips (mask prefix -> chunk mask -> rows) are folded into two:
     // the chunk's own mask bytes and the prefix words are requested together, and the source rows
     // -- which depend only on the chunk's bits, not on the destination -- are requested before the
-    // prefix count is reduced.  Every wavefront reads the chunk's <= 64 mask bytes itself.
-    const bool in_chunk = lane < chunk && t0 + lane < N;
-    const uint8_t my_keep = in_chunk ? keep[row0 + lane] : (uint8_t)0;
+    // prefix count is reduced.  Every wavefront reads the chunk's <= 64 mask bytes itself (a clamped,
+    // unconditional load: see load_byte_clamped).
+    const int in_image = N - t0 < chunk ? N - t0 : chunk;      // tokens of this chunk: >= 1
+    const bool in_chunk = lane < in_image;
+    const uint8_t my_keep = load_byte_clamped(keep + row0, lane, in_image);
     const PrefixLoads prefix = prefix_issue(keep, row0);
 
-    const bool mine = my_keep != 0;
+    const bool mine = in_chunk && my_keep != 0;
     const uint64_t bits = __ballot(mine);
     const int in_chunk_count = __popcll(bits);
 
@@ -136,24 +139,33 @@ void unpack_scatter_kernel(const uint4* __restrict__ src, const int32_t* __restr
 __global__ __launch_bounds__(kBlockThreads)
 void unpack_fill_kernel(const uint4* __restrict__ src, const uint8_t* __restrict__ keep,
                         const int32_t* __restrict__ cu_seqlens, int N, int units,
-                        uint4* __restrict__ out, int chunk, int chunks_per_image) {
+                        uint4* __restrict__ out, int chunk, int chunks_per_image, uint32_t cpi_magic) {
     __shared__ int lds4[4];
-    const int i = blockIdx.x / chunks_per_image;
-    const int c = blockIdx.x - i * chunks_per_image;
+    uint32_t i_u, c_u;
+    divmod(blockIdx.x, (uint32_t)chunks_per_image, cpi_magic, i_u, c_u);
+    const int i = (int)i_u, c = (int)c_u;
     const int t0 = c * chunk;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
     const int row0 = i * N + t0;
 
+    // one memory round trip for everything the addresses depend on: the chunk's own mask bytes, the mask
+    // bytes in front of it and the image's first packed row are requested together
     const uint8_t* image_mask = keep + (int64_t)i * N;
+    const int live = N - t0 < chunk ? N - t0 : chunk;          // tokens of this chunk inside the image: >= 1
+    const uint8_t my_keep = load_byte_clamped(keep + row0, lane, live);
+    // (through a pointer held in vector registers, so that it is a vector load issued here with the other
+    // requests: a scalar load of it gets scheduled behind the waits of the prefix count)
+    typedef const __attribute__((address_space(1))) int32_t* global_i32_ptr;
+    global_i32_ptr first_row_ptr = (global_i32_ptr)(cu_seqlens + i);
+    asm volatile("" : "+v"(first_row_ptr));
+    const int first_row = *first_row_ptr;
     const PrefixLoads prefix = prefix_issue(image_mask, t0);
     const int rank0 = prefix_finish(image_mask, prefix, lds4);
-    const int64_t base = (int64_t)cu_seqlens[i] + rank0;
+    const int64_t base = (int64_t)first_row + rank0;
 
-    const bool valid = lane < chunk && t0 + lane < N;
-    const bool mine = valid && keep[row0 + lane] != 0;
+    const bool mine = lane < live && my_keep != 0;
     const uint64_t bits = __ballot(mine);
-    const int live = __popcll(__ballot(valid));                // tokens of this chunk inside the image
 
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
     for (int t = wave; t < live; t += 4) {
@@ -186,11 +198,11 @@ void repack_kernel(const uint4* __restrict__ packed_in, const uint8_t* __restric
     const int t_in = cu_in[B];
     // requested before t_in is known: both ranges lie inside the cap_in bytes of keep_rows
     const bool in_cap = lane < chunk && r0 + lane < cap_in;
-    const uint8_t my_keep = in_cap ? keep_rows[r0 + lane] : (uint8_t)0;
+    const uint8_t my_keep = load_byte_clamped(keep_rows, (int)r0 + lane, (int)cap_in);    // looked at if in_cap
     const PrefixLoads prefix = prefix_issue(keep_rows, (int)r0);
     if (r0 > t_in) return;                                     // whole group; rows >= t_in do not exist
 
-    const bool mine = my_keep != 0 && r0 + lane < t_in;
+    const bool mine = in_cap && my_keep != 0 && r0 + lane < t_in;
     const uint64_t bits = __ballot(mine);
     const int P = prefix_finish(keep_rows, prefix, lds4);      // kept rows before this chunk
 
@@ -243,7 +255,8 @@ hipError_t launch_pack(const void* x, const uint8_t* keep, int B, int N, int C, 
     const bool early = chunk <= 4 * kMaxEarly && C / 8 <= 2 * kWaveSize && (int64_t)B * N <= 16384;
     const hipError_t err = launch_kernel(early ? pack_kernel<true> : pack_kernel<false>, dim3(B * cpi),
                        dim3(kBlockThreads), stream, static_cast<const uint4*>(x), keep, N, C / 8,
-                       static_cast<uint4*>(packed), cap_rows, cu_seqlens, gather_idx, chunk, cpi);
+                       static_cast<uint4*>(packed), cap_rows, cu_seqlens, gather_idx, chunk, cpi,
+                       div_magic((uint32_t)cpi));
     return err;
 }
 
@@ -262,7 +275,7 @@ hipError_t launch_unpack(const void* src, const uint8_t* keep, const int32_t* cu
         const int cpi = (N + chunk - 1) / chunk;
         err = launch_kernel(unpack_fill_kernel, dim3(B * cpi), dim3(kBlockThreads), stream,
                            static_cast<const uint4*>(src), keep, cu_seqlens, N, C / 8,
-                           static_cast<uint4*>(out), chunk, cpi);
+                           static_cast<uint4*>(out), chunk, cpi, div_magic((uint32_t)cpi));
     }
     return err;
 }

@@ -15,6 +15,13 @@ inline bool is16bit(ragged_dtype dt) { return dt == RAGGED_F16 || dt == RAGGED_B
 // B*N rows must be indexable with int32 (gather_idx and cu_seqlens are int32).
 inline bool rows_fit(int B, int N) { return (int64_t)B * N <= (int64_t)INT32_MAX; }
 
+// The attention grid is (pairs of a dispatch batch, 64-row q-tiles, batches of 512 (image, head) pairs): the
+// second and third dimension of a grid hold at most 65535, the whole grid fewer than 2^31 work-groups.
+inline bool grid_fits(int B, int H, int bound) {
+    const int64_t q_tiles = ((int64_t)bound + 63) / 64, batches = ((int64_t)B * H + 511) / 512;
+    return q_tiles <= 65535 && batches <= 65535 && batches * 512 * q_tiles <= (int64_t)INT32_MAX;
+}
+
 inline int from_hip(hipError_t e) { return e == hipSuccess ? RAGGED_OK : RAGGED_ERR_HIP; }
 
 // ragged_attn, ragged_attn_strided and ragged_attn_checked share the checks and the launch; flags may be null
@@ -24,12 +31,12 @@ int attn_call(const void* q, const void* k, const void* v, void* o,
               ragged_dtype in_dt, ragged_dtype out_dt, int32_t* flags, void* stream) {
     if (!q || !k || !v || !o || !cu_seqlens) return RAGGED_ERR_NULL;
     if (B <= 0 || H <= 0 || D <= 0 || max_seqlen < 1) return RAGGED_ERR_SHAPE;
-    // grid <= q-tiles * (B*H rounded up to a whole dispatch batch of 512) must fit a 32-bit grid
-    const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)max_seqlen + 63) / 64);
-    if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
+    if (!grid_fits(B, H, max_seqlen)) return RAGGED_ERR_SHAPE;
     const int64_t row = (int64_t)H * D;
-    // the kernel addresses the 64 rows of a K/V tile with 32-bit byte offsets
-    if (in_tok_stride < row || out_tok_stride < row || in_tok_stride > (int64_t)1 << 23) return RAGGED_ERR_SHAPE;
+    // the kernel addresses the 64 rows of a K/V tile with 32-bit byte offsets and takes the strides as int32
+    if (in_tok_stride < row || out_tok_stride < row || in_tok_stride > (int64_t)1 << 23 ||
+        out_tok_stride > (int64_t)INT32_MAX)
+        return RAGGED_ERR_SHAPE;
     if (D != 64) return RAGGED_ERR_UNSUPPORTED;
     const bool pair_ok = (in_dt == RAGGED_F16 && (out_dt == RAGGED_F16 || out_dt == RAGGED_F32)) ||
                          (in_dt == RAGGED_BF16 && (out_dt == RAGGED_BF16 || out_dt == RAGGED_F32));
@@ -89,8 +96,7 @@ int ragged_attn_padded(const void* q, const void* k, const void* v, void* o, con
                        ragged_dtype out_dt, int fill_mode, void* stream) {
     if (!q || !k || !v || !o || !keep) return RAGGED_ERR_NULL;
     if (B <= 0 || N <= 0 || H <= 0 || D <= 0 || !rows_fit(B, N)) return RAGGED_ERR_SHAPE;
-    const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)N + 63) / 64);
-    if (groups > (int64_t)INT32_MAX) return RAGGED_ERR_SHAPE;
+    if (!grid_fits(B, H, N)) return RAGGED_ERR_SHAPE;
     if (D != 64 || N > ragged::attn_padded_max_tokens()) return RAGGED_ERR_UNSUPPORTED;
     // the kernel addresses the N rows of an image with 32-bit byte offsets
     if ((int64_t)N * H * D * 2 >= (int64_t)1 << 31) return RAGGED_ERR_SHAPE;
@@ -109,8 +115,7 @@ int ragged_pack_attn_unpack(const void* x, const uint8_t* keep, const void* q, c
                             int fill_mode, void* stream) {
     if (!x || !keep || !q || !k || !v || !packed || !cu_seqlens || !gather_idx || !o || !out) return RAGGED_ERR_NULL;
     if (B <= 0 || N <= 0 || H <= 0 || D <= 0 || !rows_fit(B, N)) return RAGGED_ERR_SHAPE;
-    const int64_t groups = ((int64_t)B * H + 512) * (((int64_t)N + 63) / 64);
-    if (groups > (int64_t)INT32_MAX || (int64_t)N * H * D * 2 >= (int64_t)1 << 31) return RAGGED_ERR_SHAPE;
+    if (!grid_fits(B, H, N) || (int64_t)N * H * D * 2 >= (int64_t)1 << 31) return RAGGED_ERR_SHAPE;
     if (D != 64 || N > ragged::attn_padded_max_tokens() || !is16bit(dt)) return RAGGED_ERR_UNSUPPORTED;
     if ((fill_mode != 0 && fill_mode != 1) || !isfinite(scale)) return RAGGED_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(packed) || !aligned16(o) ||

@@ -67,6 +67,9 @@ def test_attn_validation(lib):
         assert _attn(lib, **{null: None}) == 1
     for bad in (dict(B=0), dict(H=0), dict(D=0), dict(ms=0), dict(B=1 << 30, H=64)):
         assert _attn(lib, **bad) == 2
+    # grid limits: 65535 q-tiles of 64 rows, 65535 dispatch batches of 512 (image, head) pairs, < 2^31 work-groups
+    for bad in (dict(B=1, H=1, ms=64 * 65535 + 1), dict(B=512 * 65535 + 1, H=1, ms=8), dict(B=1 << 16, H=16, ms=1 << 17)):
+        assert _attn(lib, **bad) == 2
     for bad in (dict(D=48), dict(i=2), dict(i=0, od=1), dict(i=1, od=0), dict(scale=float("inf")),
                 dict(scale=float("nan")), dict(q=FAKE + 4), dict(o=FAKE + 8)):
         assert _attn(lib, **bad) == 3
@@ -99,7 +102,8 @@ def test_attn_strided_validation(lib):
         return lib.ragged_attn_strided(q, k, v, o, cu, B, ms, H, D, si, so, scale, i, od, None)
     for null in ("q", "k", "v", "o", "cu"):
         assert call(**{null: None}) == 1
-    for bad in (dict(B=0), dict(ms=0), dict(si=127), dict(so=64), dict(si=-384), dict(si=(1 << 23) + 8)):
+    for bad in (dict(B=0), dict(ms=0), dict(si=127), dict(so=64), dict(si=-384), dict(si=(1 << 23) + 8),
+                dict(so=1 << 31)):
         assert call(**bad) == 2
     for bad in (dict(D=32), dict(si=132), dict(so=132), dict(i=0, od=1), dict(scale=float("inf")), dict(k=FAKE + 2)):
         assert call(**bad) == 3
