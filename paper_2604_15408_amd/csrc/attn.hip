@@ -374,30 +374,42 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         // Count first (one barrier): a group learns the image's length n before anything else is built, and
         // the groups of the upper-bound grid that have no rows leave here.
         const bool zero_fill = fill_mode == 1 && m_tile == 0;  // this group zeroes the head's slice of the dropped rows
+        // kStep, q-tile 0 (with short sequences: the groups that have rows): the count of the kept tokens in front of
+        // the image shares the barrier of the length count, so the group knows s and n together.  The other q-tiles
+        // count it after the test that lets most of them leave.
+        const bool early_s = MODE == kStep && m_tile == 0;
+        if (early_s) prefix_post(prefix_count_thread(keep, before_image), lds4);
+        // Every mask byte counts as used here, also those of rounds beyond n_tok: a load that the compiler still
+        // believes in flight makes it wait for ALL memory traffic (K/V and Q rows by then) before the register is
+        // reused further down.
+#pragma unroll
+        for (int j = 0; j < kRounds; ++j) asm volatile("" : : "v"((uint32_t)raw[j]));
+        // (the loops over the rounds leave at the first round beyond n_tok: one scalar branch instead of a
+        // skipped block per round -- a taken branch costs as much as a dozen instructions here)
         uint64_t bits[kRounds];
 #pragma unroll
-        for (int j = 0; j < kRounds; ++j)
-            if (j * kThreads < n_tok) {
-                bits[j] = __ballot(j * kThreads + tid < n_tok && raw[j] != 0);
-                if (lane == 0) {
-                    wave_cnt[j * WAVES + wave] = __popcll(bits[j]);
-                    if (zero_fill) keep_bits[j * WAVES + wave] = bits[j];
-                }
+        for (int j = 0; j < kRounds; ++j) {
+            if (j * kThreads >= n_tok) break;                  // group-uniform
+            bits[j] = __ballot(j * kThreads + tid < n_tok && raw[j] != 0);
+            if (lane == 0) {
+                wave_cnt[j * WAVES + wave] = __popcll(bits[j]);
+                if (zero_fill) keep_bits[j * WAVES + wave] = bits[j];
             }
+        }
         __syncthreads();
         n = 0;
         int before[kRounds];                                   // kept tokens in front of this wavefront's 64 of round j
 #pragma unroll
-        for (int j = 0; j < kRounds; ++j)
-            if (j * kThreads < n_tok) {
-                before[j] = n;
+        for (int j = 0; j < kRounds; ++j) {
+            if (j * kThreads >= n_tok) break;
+            before[j] = n;
 #pragma unroll
-                for (int w2 = 0; w2 < WAVES; ++w2) {
-                    const int c = wave_cnt[j * WAVES + w2];
-                    before[j] += w2 < wave ? c : 0;
-                    n += c;
-                }
+            for (int w2 = 0; w2 < WAVES; ++w2) {
+                const int c = wave_cnt[j * WAVES + w2];
+                before[j] += w2 < wave ? c : 0;
+                n += c;
             }
+        }
         if (zero_fill) {                                       // token t's keep bit: entry t / 64, bit t % 64
             if (MODE == kStep) {
                 for (int t = tid / 8; t < n_tok; t += kThreads / 8)
@@ -415,12 +427,16 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         // a group with no rows that does not write cu_seqlens either is done (whole group, before any further barrier)
         if (m0 >= n && !(MODE == kStep && h == 0 && m_tile == 0)) return;
 #pragma unroll
-        for (int j = 0; j < kRounds; ++j)
-            if (j * kThreads < n_tok && ((bits[j] >> lane) & 1ull) != 0)
+        for (int j = 0; j < kRounds; ++j) {
+            if (j * kThreads >= n_tok) break;
+            if (((bits[j] >> lane) & 1ull) != 0)
                 idx_lds[before[j] + __popcll(bits[j] & ((1ull << lane) - 1ull))] = (uint16_t)(j * kThreads + tid);
+        }
         if (MODE == kStep) {
-            s = prefix_finish(keep, before_image, lds4);       // kept tokens of the images before this one; its
-            s = __builtin_amdgcn_readfirstlane(s);             // barrier also publishes idx_lds
+            // kept tokens of the images before this one; q-tile 0 publishes idx_lds with a barrier further down, once
+            // its K/V and Q rows (which need s, not the list) are requested; for the others this barrier does
+            s = early_s ? prefix_total(lds4) : prefix_finish(keep, before_image, lds4);
+            s = __builtin_amdgcn_readfirstlane(s);
             if (h == 0 && m_tile == 0 && tid == 0) {
                 if (img == 0) step.cu_seqlens[0] = 0;
                 step.cu_seqlens[img + 1] = s + n;
@@ -503,20 +519,6 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         for (int d = 0; d < kRing - 2; ++d) c_next[d] = d + 1 < tiles ? issue(d + 1, d + 1) : 0;
     }
 
-    // ---- kStep: this head's slice of the group's 64 rows of x (two 16-byte units per thread) is requested
-    // now and stored to the packed buffer after the first tile; head 0 also records the source rows
-    uint4 x_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
-    if (MODE == kStep) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int j = m0 + 32 * i + (tid >> 3);
-            if ((!SPLIT || 32 * i + (tid >> 3) < kBM) && j < n)
-                x_raw[i] = reinterpret_cast<const uint4*>(step.x + (pad0 + idx_lds[j]) * tok + head_off)[tid & 7];
-        }
-        if (h == 0 && tid < kBM && m0 + tid < n && (int64_t)s + m0 + tid < step.cap_rows)
-            step.gather_idx[s + m0 + tid] = (int32_t)(pad0 + idx_lds[m0 + tid]);
-    }
-
     // ---- Q: this lane's query row, head-dim elements 16g .. 16g+15 (zeros past the sequence end)
     uint4 q_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
     if (q_row < n) {
@@ -532,6 +534,21 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         }
     }
     const vec8 q_frag[2] = {as_vec8<vec8>(q_raw[0]), as_vec8<vec8>(q_raw[1])};
+
+    // ---- kStep: this head's slice of the group's 64 rows of x (two 16-byte units per thread) is requested
+    // now and stored to the packed buffer after the first tile; head 0 also records the source rows
+    uint4 x_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+    if (MODE == kStep) {
+        if (m_tile == 0) __syncthreads();                      // idx_lds complete (see the prefix count above)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = m0 + 32 * i + (tid >> 3);
+            if ((!SPLIT || 32 * i + (tid >> 3) < kBM) && j < n)
+                x_raw[i] = reinterpret_cast<const uint4*>(step.x + (pad0 + idx_lds[j]) * tok + head_off)[tid & 7];
+        }
+        if (h == 0 && tid < kBM && m0 + tid < n && (int64_t)s + m0 + tid < step.cap_rows)
+            step.gather_idx[s + m0 + tid] = (int32_t)(pad0 + idx_lds[m0 + tid]);
+    }
 
     // ---- LDS read addresses of this lane inside a tile (see the header comment)
     //   K operand: row col (+16kt), chunk 2g + ks at position (2g + ks) ^ ((col>>1)&3)

@@ -74,8 +74,11 @@ __device__ __forceinline__ PrefixLoads prefix_issue(const uint8_t* __restrict__ 
     const int mis = (int)((uintptr_t)base & 15u);
     p.head = mis ? 16 - mis : 0;
     if (p.head > len) p.head = len;
-    p.body = (len - p.head) >> 4;                             // whole 16-byte words
-    p.len = len;
+    // base and len are the same for the whole group: kept in scalar registers, so that the tests on them are
+    // scalar branches
+    p.head = __builtin_amdgcn_readfirstlane(p.head);
+    p.body = __builtin_amdgcn_readfirstlane((len - p.head) >> 4);   // whole 16-byte words
+    p.len = __builtin_amdgcn_readfirstlane(len);
     const uint4* words = reinterpret_cast<const uint4*>(base + p.head);
 #pragma unroll
     for (int j = 0; j < kPrefixWords; ++j)
@@ -89,13 +92,17 @@ __device__ __forceinline__ int count_word(uint4 v) {
     return nonzero_bytes(v.x) + nonzero_bytes(v.y) + nonzero_bytes(v.z) + nonzero_bytes(v.w);
 }
 
-__device__ inline int prefix_finish(const uint8_t* __restrict__ base, const PrefixLoads& p, int* lds4) {
+// This thread's share of the count: the words and bytes requested by prefix_issue() plus, for ranges beyond
+// 16 KB, the rest of the body.
+__device__ inline int prefix_count_thread(const uint8_t* __restrict__ base, const PrefixLoads& p) {
     const int tid = threadIdx.x;
     const int tail0 = p.head + (p.body << 4);
     int count = (tid < p.head && p.hb != 0) + (tail0 + tid < p.len && p.tb != 0);
 #pragma unroll
-    for (int j = 0; j < kPrefixWords; ++j)
-        if (j * kBlockThreads < p.body) count += count_word(p.w[j]);      // group-uniform: skip absent passes
+    for (int j = 0; j < kPrefixWords; ++j) {
+        if (j * kBlockThreads >= p.body) break;                // group-uniform: no further pass holds a word
+        count += count_word(p.w[j]);
+    }
     const uint4* words = reinterpret_cast<const uint4*>(base + p.head);
     for (int w0 = tid + kPrefixWords * kBlockThreads; w0 < p.body; w0 += kPrefixWords * kBlockThreads) {
         uint4 more[kPrefixWords];                             // all loads of a pass issued before any is used
@@ -105,10 +112,22 @@ __device__ inline int prefix_finish(const uint8_t* __restrict__ base, const Pref
 #pragma unroll
         for (int j = 0; j < kPrefixWords; ++j) count += count_word(more[j]);
     }
-    count = wave_sum(count);
-    if ((tid & (kWaveSize - 1)) == 0) lds4[tid >> 6] = count; // lds4 is used once per kernel
+    return count;
+}
+
+// The reduction over the group in two steps, for callers that have a barrier of their own to share:
+// prefix_post() before it (every thread), prefix_total() after it.  lds4 is used once per kernel.
+__device__ __forceinline__ void prefix_post(int thread_count, int* lds4) {
+    const int tid = threadIdx.x;
+    const int count = wave_sum(thread_count);
+    if ((tid & (kWaveSize - 1)) == 0) lds4[tid >> 6] = count;
+}
+__device__ __forceinline__ int prefix_total(const int* lds4) { return lds4[0] + lds4[1] + lds4[2] + lds4[3]; }
+
+__device__ inline int prefix_finish(const uint8_t* __restrict__ base, const PrefixLoads& p, int* lds4) {
+    prefix_post(prefix_count_thread(base, p), lds4);
     __syncthreads();
-    return lds4[0] + lds4[1] + lds4[2] + lds4[3];
+    return prefix_total(lds4);
 }
 
 }  // namespace ragged
