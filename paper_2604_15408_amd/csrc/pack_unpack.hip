@@ -34,7 +34,7 @@ void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, 
     const int i = (int)i_u, c = (int)c_u;
     const int t0 = c * chunk;
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // in a scalar register: the bit walks below are scalar code
     const int row0 = i * N + t0;                               // flat index of the chunk's first token
 
     // Three dependent fabric round trips (mask prefix -> chunk mask -> rows) are folded into two:
@@ -54,19 +54,27 @@ void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, 
     // Rows of the chunk are dealt to the four wavefronts round-robin: set bit k -> wavefront k%4.
     // EARLY (chunk <= 16 and rows of at most 128 16-byte words): a wavefront has at most four rows
     // of two words per lane and requests them now, into registers.
+    // (the walks over the set bits are straight-line scalar code: a taken branch costs as much as a dozen
+    // instructions, so no loop per dropped bit)
     uint4 held[kMaxEarly][2];
     if (EARLY) {
 #pragma unroll
         for (int r = 0; r < kMaxEarly; ++r) {
             held[r][0] = make_uint4(0u, 0u, 0u, 0u);
             held[r][1] = make_uint4(0u, 0u, 0u, 0u);
-            const int k = wave + 4 * r;                        // this wavefront's r-th row is set bit k
-            if (k < in_chunk_count) {
-                uint64_t m = bits;
-                for (int z = 0; z < k; ++z) m &= m - 1;        // drop the k lowest set bits (k < 16)
-                const uint4* src = x + (int64_t)(row0 + __builtin_ctzll(m)) * units;
+        }
+        if (wave < in_chunk_count) {                           // this wavefront has a row: set bits wave, wave + 4, ...
+            uint32_t m = (uint32_t)bits;                       // chunk <= 16 here: the bits fit
+#pragma unroll
+            for (int z = 0; z < 3; ++z) m = z < wave ? (m & (m - 1)) : m;   // drop the `wave` lowest set bits
+#pragma unroll
+            for (int r = 0; r < kMaxEarly; ++r) {
+                const uint4* src = x + (int64_t)(row0 + __builtin_ctz(m)) * units;
                 if (lane < units) held[r][0] = src[lane];
                 if (lane + kWaveSize < units) held[r][1] = src[lane + kWaveSize];
+                if (wave + 4 * (r + 1) >= in_chunk_count) break;
+#pragma unroll
+                for (int z = 0; z < 4; ++z) m &= m - 1;        // on to set bit wave + 4(r+1)
             }
         }
     }
@@ -96,13 +104,15 @@ void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, 
         }
     } else {
         uint64_t rest = bits;
-        for (int k = 0; rest != 0; ++k) {
+#pragma unroll
+        for (int z = 0; z < 3; ++z) rest = z < wave ? (rest & (rest - 1)) : rest;
+        for (int k = wave; rest != 0; k += 4) {                // one iteration per row of this wavefront
             const int t = __builtin_ctzll(rest);
-            rest &= rest - 1;
-            if ((k & 3) != wave) continue;
             const int64_t dst = (int64_t)P + k;
             if (dst >= cap_rows) break;
             wave_copy_row(x + (int64_t)(row0 + t) * units, packed + dst * units, units, lane);
+#pragma unroll
+            for (int z = 0; z < 4; ++z) rest &= rest - 1;
         }
     }
 }
@@ -119,7 +129,7 @@ void unpack_scatter_kernel(const uint4* __restrict__ src, const int32_t* __restr
                            uint4* __restrict__ out) {
     const int T = cu_seqlens[B];
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r0 = blockIdx.x * kUnpackRows;
     if (r0 >= T) return;
 #pragma unroll
@@ -146,7 +156,7 @@ void unpack_fill_kernel(const uint4* __restrict__ src, const uint8_t* __restrict
     const int i = (int)i_u, c = (int)c_u;
     const int t0 = c * chunk;
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row0 = i * N + t0;
 
     // one memory round trip for everything the addresses depend on: the chunk's own mask bytes, the mask
@@ -193,7 +203,7 @@ void repack_kernel(const uint4* __restrict__ packed_in, const uint8_t* __restric
                    int32_t* __restrict__ gather_out, int chunk) {
     __shared__ int lds4[4];
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t r0 = (int64_t)blockIdx.x * chunk;            // <= cap_in by the grid size
     const int t_in = cu_in[B];
     // requested before t_in is known: both ranges lie inside the cap_in bytes of keep_rows
@@ -215,13 +225,15 @@ void repack_kernel(const uint4* __restrict__ packed_in, const uint8_t* __restric
         if (c >= r0 && c < r0 + chunk) cu_out[i] = P + __popcll(bits & ((1ull << (int)(c - r0)) - 1ull));
     }
     uint64_t rest = bits;
-    for (int k = 0; rest != 0; ++k) {
+#pragma unroll
+    for (int z = 0; z < 3; ++z) rest = z < wave ? (rest & (rest - 1)) : rest;   // drop the `wave` lowest set bits
+    for (int k = wave; rest != 0; k += 4) {                    // one iteration per row of this wavefront
         const int t = __builtin_ctzll(rest);
-        rest &= rest - 1;
-        if ((k & 3) != wave) continue;
         const int64_t dst = (int64_t)P + k;
         if (dst >= cap_out) break;
         wave_copy_row(packed_in + (r0 + t) * units, packed_out + dst * units, units, lane);
+#pragma unroll
+        for (int z = 0; z < 4; ++z) rest &= rest - 1;
     }
 }
 
