@@ -287,12 +287,10 @@ __device__ __forceinline__ void tile_any(int rem, uint32_t tile0, uint32_t k_rel
 //   dropped rows of o.
 // MODE kStep  : the whole pack -> attention -> unpack step in this one launch.  q, k, v, o are
 //   packed as in kPacked, but the image's first row s is recounted from the keep mask (nonzero
-//   bytes before the image) and the kept-position list is built as in kPadded.  The group (image,
-//   head, q-tile) writes each output row of its q-tile twice: to o (packed) and to its padded
-//   position in `out`; it also moves that head's 128-byte slice of 64 rows from x to the packed
-//   buffer: its own rows, or -- when the image has fewer q-tiles than the grid -- those of the
-//   q-tile before its own, so that the copy runs beside the attention instead of in front of it.
-//   The head-0 groups also write gather_idx for the rows they copy, and q-tile 0 of head 0 writes
+//   bytes before the image) and the kept-position list is built as in kPadded.  Besides its
+//   attention rows the group (image, head, q-tile) moves that head's 128-byte slice of its 64 rows
+//   from x to the packed buffer and writes each output row twice: to o (packed) and to its padded
+//   position in `out`.  Head-0 groups also write gather_idx, and q-tile 0 of head 0 writes
 //   cu_seqlens.  Every group derives s and the list itself, so no group waits for another.
 enum { kPacked = 0, kPadded = 1, kStep = 2 };
 
@@ -361,8 +359,6 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
     __shared__ uint64_t keep_bits[LIST ? kRounds * WAVES : 1];     // fill_mode 1: keep bits of tokens 64e .. 64e+63 in entry e
     __shared__ int lds4[4];
     int s, n;
-    int cm0 = 0;                                               // kStep: first row of the q-tile this group copies ...
-    bool copies = false;                                       // ... if it copies any (group-uniform)
     if (LIST) {
         constexpr int kThreads = kAttnThreads;
         static_assert(kRounds * kThreads == kMaxGatherTokens, "the mask of an image is read in whole rounds of the group");
@@ -428,19 +424,8 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
             }
         }
         n = __builtin_amdgcn_readfirstlane(n);
-        if (MODE == kStep) {
-            // Which rows this group moves from x to the packed buffer.  When the image has fewer q-tiles than the
-            // grid (pruned sequences), the groups behind the last real q-tile have nothing to attend to: every group
-            // then copies the rows of the q-tile BEFORE its own, so the rows of q-tile 0 -- with short sequences the
-            // only ones -- are copied beside their attention instead of in front of it.  Otherwise a group copies
-            // the rows of its own q-tile.
-            const bool spare = (n + kBM - 1) / kBM < (int)gridDim.y;
-            cm0 = spare ? m0 - kBM : m0;
-            copies = cm0 >= 0 && cm0 < n;
-        }
-        // a group with no rows (kStep: none to attend to and none to copy) that does not write cu_seqlens either
-        // is done (whole group, before any further barrier)
-        if (m0 >= n && !(MODE == kStep && (copies || (h == 0 && m_tile == 0)))) return;
+        // a group with no rows that does not write cu_seqlens either is done (whole group, before any further barrier)
+        if (m0 >= n && !(MODE == kStep && h == 0 && m_tile == 0)) return;
 #pragma unroll
         for (int j = 0; j < kRounds; ++j) {
             if (j * kThreads >= n_tok) break;
@@ -467,36 +452,8 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
             atomicOr(step.flags, RAGGED_FLAG_SEQLEN_EXCEEDED);
     }
     n = __builtin_amdgcn_readfirstlane(n);
+    if (m0 >= n) return;                                       // whole group exits together
     const int64_t pad0 = (int64_t)img * n_tok;                 // first padded row of the image (kStep)
-    // kStep: this head's 128-byte slice of the rows cm0 .. cm0 + kBM - 1 (eight 16-byte units per row, 32 rows per
-    // pass of the group); head 0 also records the source rows
-    uint4 x_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
-    auto load_x_rows = [&]() {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int j = cm0 + 32 * i + (tid >> 3);
-            if ((!SPLIT || 32 * i + (tid >> 3) < kBM) && j < n)
-                x_raw[i] = reinterpret_cast<const uint4*>(step.x + (pad0 + idx_lds[j]) * tok + head_off)[tid & 7];
-        }
-        if (h == 0 && tid < kBM && cm0 + tid < n && (int64_t)s + cm0 + tid < step.cap_rows)
-            step.gather_idx[s + cm0 + tid] = (int32_t)(pad0 + idx_lds[cm0 + tid]);
-    };
-    auto store_packed_rows = [&]() {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int j = cm0 + 32 * i + (tid >> 3);
-            if ((!SPLIT || 32 * i + (tid >> 3) < kBM) && j < n && (int64_t)s + j < step.cap_rows)
-                reinterpret_cast<uint4*>(step.packed + ((int64_t)s + j) * tok + head_off)[tid & 7] = x_raw[i];
-        }
-    };
-    if (m0 >= n) {                                             // whole group: no rows to attend to
-        // (kStep: such a group is not q-tile 0, so the barrier of its prefix count has published the list)
-        if (MODE == kStep && copies) {
-            load_x_rows();
-            store_packed_rows();
-        }
-        return;
-    }
     // row of the j-th token of this image in q / k / v / o
     auto row_of = [&](int j) -> int64_t { return GATHER ? (int64_t)s + idx_lds[j] : (int64_t)s + j; };
     const int q_row = m0 + (SPLIT ? 0 : wave * 16) + col;      // this lane's query inside the image
@@ -578,10 +535,19 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
     }
     const vec8 q_frag[2] = {as_vec8<vec8>(q_raw[0]), as_vec8<vec8>(q_raw[1])};
 
-    // ---- kStep: the rows this group copies are requested now and stored after the first tile
+    // ---- kStep: this head's slice of the group's 64 rows of x (two 16-byte units per thread) is requested
+    // now and stored to the packed buffer after the first tile; head 0 also records the source rows
+    uint4 x_raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
     if (MODE == kStep) {
         if (m_tile == 0) __syncthreads();                      // idx_lds complete (see the prefix count above)
-        if (copies) load_x_rows();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = m0 + 32 * i + (tid >> 3);
+            if ((!SPLIT || 32 * i + (tid >> 3) < kBM) && j < n)
+                x_raw[i] = reinterpret_cast<const uint4*>(step.x + (pad0 + idx_lds[j]) * tok + head_off)[tid & 7];
+        }
+        if (h == 0 && tid < kBM && m0 + tid < n && (int64_t)s + m0 + tid < step.cap_rows)
+            step.gather_idx[s + m0 + tid] = (int32_t)(pad0 + idx_lds[m0 + tid]);
     }
 
     // ---- LDS read addresses of this lane inside a tile (see the header comment)
@@ -607,6 +573,15 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         for (int dt = 0; dt < 4; ++dt) o_acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // kStep: the x rows requested above go to the packed buffer
+    auto store_packed_rows = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = m0 + 32 * i + (tid >> 3);
+            if ((!SPLIT || 32 * i + (tid >> 3) < kBM) && j < n && (int64_t)s + j < step.cap_rows)
+                reinterpret_cast<uint4*>(step.packed + ((int64_t)s + j) * tok + head_off)[tid & 7] = x_raw[i];
+        }
+    };
     if (SPLIT) {
         // ---- this wavefront's tiles wave, wave + 4, ...: its own slot, its own loads, no barrier
         const uint32_t tile0 = ring0 + wave * 2 * kTileBytes;
@@ -625,7 +600,7 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) o_acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        if (MODE == kStep && copies) store_packed_rows();
+        if (MODE == kStep) store_packed_rows();
         if (tiles == 1) {                   // a single tile: wavefront 0 holds the whole result, nothing to merge
             if (wave == 0 && q_row < n) {
                 const bool row_fits = MODE != kStep || (int64_t)s + q_row < step.cap_rows;
@@ -736,12 +711,11 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
                     }
                 }
             }
-            if (t == 0 && copies) {
+            if (t == 0) {
                 // the x rows have long arrived: with several tiles the copy drains while the rest is computed
-                // (store_packed_rows() written out: see PEEL above)
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const int j = cm0 + 32 * i + (tid >> 3);
+                    const int j = m0 + 32 * i + (tid >> 3);
                     if (j < n && (int64_t)s + j < step.cap_rows)
                         reinterpret_cast<uint4*>(step.packed + ((int64_t)s + j) * tok + head_off)[tid & 7] = x_raw[i];
                 }
