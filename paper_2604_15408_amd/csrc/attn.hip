@@ -58,6 +58,14 @@ constexpr int kAttnWaves = 4;           // wavefronts per work-group: 4 or 8 (th
 constexpr int kAttnThreads = kWaveSize * kAttnWaves;
 constexpr int kAttnOcc = kAttnWaves == 8 ? 2 : (kRing == 2 ? 4 : (kRing == 3 ? 3 : 2));  // work-groups per CU aimed at
 constexpr int kTileBytes = kBN * kHeadDim * 2;   // one K or one V tile: 8 KB
+// A sequence's LAST tile takes a tail of up to 16 keys along (n = 64k + 1 .. 64k + 16, k >= 2): 80 keys in one
+// pass instead of a pass of its own for a handful of keys -- ViT lengths are 64k + 1 before pruning (197, 577).
+// (Not for k = 1: the first tile of a sequence has a form of its own, and a second copy of it for 80 keys
+// costs the short launches more in code than the few sequences of 65..80 tokens gain.)
+// The tail's K rows and V rows live behind the ring.
+constexpr int kExtraRows = 16;
+constexpr int kExtraBytes = 2 * kExtraRows * kHeadDim * 2;   // K rows, then V rows: 4 KB
+constexpr bool kExtTail = kRing == 2;            // (the load bookkeeping of deeper rings does not count the tail's loads)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazyLog2 = 8.0f;       // probabilities stay below 2^8 between rescales
 constexpr int kSplitMaxGroups = 256;    // launches of at most this many 64-row q-tiles split the keys over the wavefronts
@@ -159,7 +167,9 @@ __device__ __forceinline__ float quad_max(float x) {
     return fmaxf(as_f32(b0), as_f32(b1));
 }
 // One K/V tile (already in LDS) against this wavefront's 16 queries: S^T = K Q^T, online-softmax
-// update, O^T += V^T P^T.  NT = 16-key subtiles present in the tile (1..4); MASK: the last subtile may
+// update, O^T += V^T P^T.  NT = 16-key subtiles present in the tile (1..4, or 5: a full tile plus the tail
+// subtile kept behind the ring, whose K / transposed V operand addresses are ek_a0 / ev_a0 -- the second
+// k-step / head-dim pair is at the address xor 16, as for the tile itself); MASK: the last subtile may
 // hold keys past the end of the sequence (index >= rem), which are masked out (their LDS rows hold
 // a copy of the last real row, so they are finite wherever the inputs are).
 // k_a0/k_a1: this lane's LDS byte addresses of its K operand for the two 32-element k-steps of
@@ -171,6 +181,7 @@ __device__ __forceinline__ float quad_max(float x) {
 // values through alpha = exp2(-inf) = 0 and accumulators cleared beforehand.)
 template <typename In, int NT, bool MASK, bool FIRST>
 __device__ __forceinline__ void tile_update(uint32_t k_a0, uint32_t k_a1, uint32_t v_a0, uint32_t v_a1,
+                                            uint32_t ek_a0, uint32_t ev_a0,
                                             const typename In::vec8 (&q_frag)[2], int rem, int g,
                                             float scale_log2e, float& m_run, f32x4& l_acc,
                                             f32x4 (&o_acc)[4]) {
@@ -179,8 +190,8 @@ __device__ __forceinline__ void tile_update(uint32_t k_a0, uint32_t k_a1, uint32
     f32x4 st[NT];
 #pragma unroll
     for (int kt = 0; kt < NT; ++kt) {
-        const uint4 a0 = lds_read16(k_a0 + kt * 16 * 128);
-        const uint4 a1 = lds_read16(k_a1 + kt * 16 * 128);
+        const uint4 a0 = lds_read16(kt == 4 ? ek_a0 : k_a0 + kt * 16 * 128);
+        const uint4 a1 = lds_read16(kt == 4 ? ek_a0 ^ 16u : k_a1 + kt * 16 * 128);
         st[kt] = In::mfma(as_vec8<vec8>(a0), q_frag[0], f32x4{0.f, 0.f, 0.f, 0.f});
         st[kt] = In::mfma(as_vec8<vec8>(a1), q_frag[1], st[kt]);
     }
@@ -218,9 +229,10 @@ __device__ __forceinline__ void tile_update(uint32_t k_a0, uint32_t k_a1, uint32
             if (MASK && kt == NT - 1) p = (r < last_valid) ? p : 0.f;
             st[kt][r] = p;
         }
-    // -------- O^T += V^T P^T : 32-key blocks x four 16-row head-dim tiles (odd NT: zero upper half)
+    // -------- O^T += V^T P^T : 32-key blocks x four 16-row head-dim tiles (NT 1 or 3: zero upper half)
+    constexpr int kBlocks = NT == 5 ? 2 : (NT + 1) / 2;
 #pragma unroll
-    for (int bb = 0; bb < (NT + 1) / 2; ++bb) {
+    for (int bb = 0; bb < kBlocks; ++bb) {
         uint4 vt[4];
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
@@ -239,24 +251,40 @@ __device__ __forceinline__ void tile_update(uint32_t k_a0, uint32_t k_a1, uint32
         if (FIRST && bb == 0) pv_block<true>(In{}, vt, p, o_acc, l_acc);
         else pv_block<false>(In{}, vt, p, o_acc, l_acc);
     }
+    if (NT == 5) {
+        // the tail subtile: 16 keys in the lower half of a 32-key block whose upper half is zero on both sides
+        // (no rows are read for it)
+        uint4 vt[4];
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            const uint2 lo2 = __builtin_bit_cast(uint2, lds_read_tr(((dt & 2) ? ev_a0 ^ 16u : ev_a0) + 8 * (dt & 1)));
+            vt[dt] = make_uint4(lo2.x, lo2.y, 0u, 0u);
+        }
+        const float p[8] = {st[NT - 1][0], st[NT - 1][1], st[NT - 1][2], st[NT - 1][3], 0.f, 0.f, 0.f, 0.f};
+        pv_block<false>(In{}, vt, p, o_acc, l_acc);
+    }
 }
 
 // A tile of `rem` remaining keys at LDS address tile0: full tiles take the unmasked form, a tail is specialised
-// on its number of 16-key subtiles.  k_rel0 / v_rel0: this lane's operand offsets inside a tile.
-template <typename In, bool FIRST>
-__device__ __forceinline__ void tile_any(int rem, uint32_t tile0, uint32_t k_rel0, uint32_t v_rel0,
+// on its number of 16-key subtiles.  k_rel0 / v_rel0: this lane's operand offsets inside a tile; ext_tile: a last
+// tile of 65..80 keys whose rows 64.. are kept behind the ring at LDS address extra0 (EXT: the kernel form has them).
+template <typename In, bool FIRST, bool EXT>
+__device__ __forceinline__ void tile_any(int rem, bool ext_tile, uint32_t tile0, uint32_t extra0, uint32_t k_rel0, uint32_t v_rel0,
                                          const typename In::vec8 (&q_frag)[2], int g, float scale_log2e,
                                          float& m_run, f32x4& l_acc, f32x4 (&o_acc)[4]) {
     const uint32_t k_a0 = tile0 + k_rel0, k_a1 = tile0 + (k_rel0 ^ 16u);
     const uint32_t v_a0 = tile0 + v_rel0, v_a1 = tile0 + (v_rel0 ^ 16u);
-    if (rem >= kBN) {
-        tile_update<In, 4, false, FIRST>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc);
+    const uint32_t ek_a0 = extra0 + k_rel0, ev_a0 = extra0 + kExtraBytes / 2 + (v_rel0 - kTileBytes);
+    if (EXT && ext_tile) {
+        tile_update<In, 5, true, FIRST>(k_a0, k_a1, v_a0, v_a1, ek_a0, ev_a0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc);
+    } else if (rem >= kBN) {
+        tile_update<In, 4, false, FIRST>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc);
     } else {
         switch ((rem + 15) >> 4) {
-            case 1: tile_update<In, 1, true, FIRST>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
-            case 2: tile_update<In, 2, true, FIRST>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
-            case 3: tile_update<In, 3, true, FIRST>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
-            default: tile_update<In, 4, true, FIRST>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+            case 1: tile_update<In, 1, true, FIRST>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+            case 2: tile_update<In, 2, true, FIRST>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+            case 3: tile_update<In, 3, true, FIRST>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+            default: tile_update<In, 4, true, FIRST>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
         }
     }
 }
@@ -334,7 +362,9 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
     constexpr int kI = 8 / WAVES;                              // load instructions per wavefront per K (or V) tile
     constexpr int kPer = 2 * kI;                               // ... per K+V tile
     constexpr int kBM = SPLIT ? 16 : 16 * WAVES;               // queries per work-group
-    __shared__ __attribute__((aligned(1024))) uint4 ring[(SPLIT ? WAVES : kRing) * 2 * kTileBytes / 16];   // [slot][K|V]
+    constexpr bool EXT = kExtTail && !SPLIT;                   // a last tile may take a tail of <= 16 keys along
+    constexpr int kRingBytes = (SPLIT ? WAVES : kRing) * 2 * kTileBytes;
+    __shared__ __attribute__((aligned(1024))) uint4 ring[(kRingBytes + (EXT ? kExtraBytes : 0)) / 16];   // [slot][K|V], tail rows
 
     // grid (group, q_tiles, batches): work-groups are dispatched x-fastest, i.e. in the order
     // (batch * q_tiles + m_tile) * group + slot of the mapping described above, with no division to undo it
@@ -463,15 +493,22 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
     // the lane's LDS slot is position lane%8 of that row, which holds chunk (lane%8) ^ ((row>>1)&3).
     const uint32_t ring0 = (uint32_t)reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) void*)ring);
+    const uint32_t extra0 = ring0 + kRingBytes;                // the tail rows of a last tile (EXT)
     const uint32_t tok_bytes = (uint32_t)tok * 2u;
     const int load_key = 8 * kI * wave + (lane >> 3);          // + 8i
     const uint32_t load_chunk = 16u * ((lane & 7) ^ ((lane >> 4) & 3));
     const uint16_t* k_base = k + (int64_t)s * tok + head_off;   // wave-uniform
     const uint16_t* v_base = v + (int64_t)s * tok + head_off;
+    // tiles of 64 keys; a tail of 1 .. 16 keys behind at least two full tiles rides along with the last one (EXT)
+    // (unsigned arithmetic and a select: no branch on the way to the first loads)
+    const unsigned tail_keys = (unsigned)n & (kBN - 1);
+    const bool rides = EXT && n > 2 * kBN && tail_keys - 1u < (unsigned)kExtraRows;
+    const int tiles = (int)(((unsigned)n + kBN - 1) / kBN) - (rides ? 1 : 0);
+    const int ride_tile = rides ? tiles - 1 : -1;              // the tile that takes the tail along, if any
     // Returns the number of load instructions issued (0 or kPer).  The per-lane offset is 32 bits wide:
     // packed rows are addressed relative to the tile's first row (the 64-bit part is wave-uniform),
     // gathered rows relative to the image's first token (the host checks that N tokens fit).
-    auto issue = [&](int t, int slot) -> int {
+    auto issue = [&](int t, int slot, bool may_ride = true) -> int {
         const int rem = n - t * kBN;
         const int need_rows = rem >= kBN ? kBN : 32 * ((rem + 31) >> 5);   // rows the tile's MFMAs touch
         if (8 * kI * wave >= need_rows) return 0;
@@ -485,6 +522,15 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
             const uint32_t voff = row * tok_bytes + load_chunk;
             dma16(dst + i * 1024, voff, k_base + tile_off);
             dma16(dst + i * 1024 + kTileBytes, voff, v_base + tile_off);
+        }
+        if (__builtin_expect(may_ride && t == ride_tile && wave < kExtraRows / 8, 0)) {
+            // the tail rows 64 .. 79 of a last tile: eight rows per instruction, wavefronts 0 and 1
+            int rel = kBN + 8 * wave + (lane >> 3);
+            rel = rel < rem ? rel : rem - 1;
+            const uint32_t row = GATHER ? (uint32_t)idx_lds[t * kBN + rel] : (uint32_t)rel;
+            const uint32_t voff = row * tok_bytes + load_chunk;
+            dma16(extra0 + wave * 1024, voff, k_base + tile_off);
+            dma16(extra0 + wave * 1024 + kExtraBytes / 2, voff, v_base + tile_off);
         }
         return kPer;
     };
@@ -508,13 +554,12 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         }
     };
 
-    const int tiles = (n + kBN - 1) / kBN;
     // c_next[d] = load instructions this wavefront has in flight for tile t+1+d (prologue: tiles 1 .. kRing-2)
     int c_next[kRing > 2 ? kRing - 2 : 1] = {0};
     if (SPLIT) {
         if (wave < tiles) issue_own(wave);
     } else {
-        issue(0, 0);
+        issue(0, 0, false);                                    // (a tile that takes a tail along is never the first)
 #pragma unroll
         for (int d = 0; d < kRing - 2; ++d) c_next[d] = d + 1 < tiles ? issue(d + 1, d + 1) : 0;
     }
@@ -588,11 +633,11 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         if (wave < tiles) {
             wait_vm<0>();                   // the tile has landed (the loads were this wavefront's own)
             // its results depend on every LDS read of the tile: the slot is free after it
-            tile_any<In, PEEL>(n - wave * kBN, tile0, k_rel0, v_rel0, q_frag, g, scale_log2e, m_run, l_acc, o_acc);
+            tile_any<In, PEEL, false>(n - wave * kBN, false, tile0, 0, k_rel0, v_rel0, q_frag, g, scale_log2e, m_run, l_acc, o_acc);
             for (int t = wave + WAVES; t < tiles; t += WAVES) {
                 issue_own(t);
                 wait_vm<0>();
-                tile_any<In, false>(n - t * kBN, tile0, k_rel0, v_rel0, q_frag, g, scale_log2e, m_run, l_acc, o_acc);
+                tile_any<In, false, false>(n - t * kBN, false, tile0, 0, k_rel0, v_rel0, q_frag, g, scale_log2e, m_run, l_acc, o_acc);
             }
         } else {                            // no tile for this wavefront: it contributes nothing to the merge
             m_run = -INFINITY;
@@ -671,8 +716,9 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         for (int d = 0; d + 1 < kRing - 2; ++d) c_next[d] = c_next[d + 1];
         if (kRing > 2) c_next[kRing > 2 ? kRing - 3 : 0] = c_new;
         if (wave_active)
-            tile_any<In, decltype(first)::value>(n - t * kBN, ring0 + slot * 2 * kTileBytes, k_rel0, v_rel0, q_frag, g,
-                                                 scale_log2e, m_run, l_acc, o_acc);
+            tile_any<In, decltype(first)::value, EXT && !decltype(first)::value>(n - t * kBN, t == ride_tile,
+                                                      ring0 + slot * 2 * kTileBytes, extra0, k_rel0, v_rel0,
+                                                      q_frag, g, scale_log2e, m_run, l_acc, o_acc);
         slot = slot == kRing - 1 ? 0 : slot + 1;
     };
     if constexpr (PEEL) {
@@ -700,14 +746,17 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
                 const uint32_t tile0 = ring0 + slot * 2 * kTileBytes;
                 const uint32_t k_a0 = tile0 + k_rel0, k_a1 = tile0 + (k_rel0 ^ 16u);
                 const uint32_t v_a0 = tile0 + v_rel0, v_a1 = tile0 + (v_rel0 ^ 16u);
-                if (rem >= kBN) {
-                    tile_update<In, 4, false, false>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc);
+                const uint32_t ek_a0 = extra0 + k_rel0, ev_a0 = extra0 + kExtraBytes / 2 + (v_rel0 - kTileBytes);
+                if (t == ride_tile) {
+                    tile_update<In, 5, true, false>(k_a0, k_a1, v_a0, v_a1, ek_a0, ev_a0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc);
+                } else if (rem >= kBN) {
+                    tile_update<In, 4, false, false>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc);
                 } else {
                     switch ((rem + 15) >> 4) {
-                        case 1: tile_update<In, 1, true, false>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
-                        case 2: tile_update<In, 2, true, false>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
-                        case 3: tile_update<In, 3, true, false>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
-                        default: tile_update<In, 4, true, false>(k_a0, k_a1, v_a0, v_a1, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                        case 1: tile_update<In, 1, true, false>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                        case 2: tile_update<In, 2, true, false>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                        case 3: tile_update<In, 3, true, false>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
+                        default: tile_update<In, 4, true, false>(k_a0, k_a1, v_a0, v_a1, 0, 0, q_frag, rem, g, scale_log2e, m_run, l_acc, o_acc); break;
                     }
                 }
             }

@@ -50,6 +50,16 @@ def test_single_sequence_lengths_fp16(n):
     check([n], 2, "f16", 100 + n)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_last_tile_takes_a_tail_of_up_to_16_keys_along(dtype):
+    """Large launches (not the key-split form) run a last tile of 65..80 keys in one pass when at least two full
+    tiles precede the tail: every length around the window's edges behind one, two and three full tiles, plus the
+    64k+1 lengths of unpruned ViTs."""
+    lengths = list(range(63, 84)) + list(range(127, 147)) + [191, 192, 193, 197, 207, 208, 209, 577]
+    assert len(lengths) * 6 * 2 > 256                          # more 64-row q-tiles than the key-split form takes
+    check(lengths, 6, dtype, 4242, max_seqlen=577)
+
+
 @pytest.mark.parametrize("n", [1, 2, 17, 40, 64, 65, 197, 577])
 @pytest.mark.parametrize("out", ["same", "f32"])
 def test_single_sequence_lengths_bf16(n, out):
