@@ -121,14 +121,15 @@ def run(args):
     issue = {"one_launch_prepared": p.prepared_one_launch(), "one_launch": p.one_launch,
              "eager_prepared": p.prepared_step(), "eager": p.step, "hipgraph": g_step.replay,
              "streams3_one_launch_prepared": streamed.step}
-    t_modes, gpu_modes = {}, {}
+    t_modes, gpu_modes, enq_modes = {}, {}, {}
     for name, fn in issue.items():
         for _ in range(args.warmup):
             fn()
         if name.startswith("streams3"):               # events on one stream see only a third of these launches
             t_modes[name] = wall_blocks(torch, fn, args.steps, args.blocks)
         else:
-            t_modes[name], gpu_modes[name] = timed_blocks(torch, fn, args.steps, args.blocks)
+            t_modes[name], gpu_modes[name], enq_modes[name] = timed_blocks(torch, fn, args.steps, args.blocks,
+                                                                           with_enqueue=True)
     t_step = t_modes[HEADLINE_MODE]["median"]
 
     # ---- each kernel alone: REPLICAS back-to-back copies in one graph, HIP events around each replay
@@ -202,8 +203,12 @@ def run(args):
         "timing": {"blocks": args.blocks, "steps_per_block": block_steps(args.steps),
                    "ms_per_step_p10": t_modes[HEADLINE_MODE]["p10"] * 1e3,
                    "ms_per_step_p90": t_modes[HEADLINE_MODE]["p90"] * 1e3,
+                   "host_enqueue_us_per_step": enq_modes[HEADLINE_MODE]["median"] * 1e6,
                    "note": "value and ms_per_step are the median over the blocks; each block is a multiple of "
-                           "--steps back-to-back steps between two device synchronisations"},
+                           "--steps back-to-back steps between two device synchronisations; host_enqueue_us_per_step "
+                           "is the host time per call until the block's last call has returned (when it is as long "
+                           "as the step, the Python call rate bounds the block, not the kernel: the same loop from "
+                           "C++, ragged_call_cost, is the check)"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline(w, args.fill_mode),
         "extras": {

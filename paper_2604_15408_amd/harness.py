@@ -34,13 +34,15 @@ def wall_blocks(torch, fn, steps: int, blocks: int = BLOCKS):
     return spread([wall_steps(torch, fn, n) for _ in range(blocks)])
 
 
-def timed_blocks(torch, fn, steps: int, blocks: int = BLOCKS):
+def timed_blocks(torch, fn, steps: int, blocks: int = BLOCKS, with_enqueue: bool = False):
     """wall_blocks() with a pair of HIP events recorded on the launching stream around the calls of every
     block as well: returns (wall seconds per step, GPU microseconds per step between the two events), both as
-    spread() over the blocks.  The event time is the average duration of one launch inside the timed region,
+    spread() over the blocks; with_enqueue adds the host seconds per step until the last call of a block has
+    returned (before the synchronisation): where that equals the wall time, the host's call rate and not the
+    kernel is what the block measured.  The event time is the average duration of one launch inside the timed region,
     including whatever gap the stream leaves between consecutive kernels."""
     n = block_steps(steps)
-    wall, gpu = [], []
+    wall, gpu, enq = [], [], []
     for _ in range(blocks):
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
@@ -50,9 +52,13 @@ def timed_blocks(torch, fn, steps: int, blocks: int = BLOCKS):
         for _ in range(n):
             fn()
         e1.record()
+        t_enq = time.perf_counter()
         torch.cuda.synchronize()
         wall.append((time.perf_counter() - t0) / n)
+        enq.append((t_enq - t0) / n)
         gpu.append(e0.elapsed_time(e1) * 1e3 / n)
+    if with_enqueue:
+        return spread(wall), spread(gpu), spread(enq)
     return spread(wall), spread(gpu)
 
 
