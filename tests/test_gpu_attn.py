@@ -50,6 +50,19 @@ def test_single_sequence_lengths_fp16(n):
     check([n], 2, "f16", 100 + n)
 
 
+@pytest.mark.parametrize("H", [1, 5, 7, 16])
+def test_head_counts_and_several_dispatch_batches(H):
+    """The (image, head) pair of a work-group comes from a multiply with a host-made reciprocal of H, and pairs
+    beyond 512 go to further dispatch batches (the third grid dimension): head counts that are not the usual 12,
+    with enough images for two or three batches."""
+    B = 1100 // H + 3
+    rng = np.random.default_rng(77 + H)
+    lengths = [int(v) for v in rng.integers(0, 70, size=B)]
+    lengths[0], lengths[-1] = 69, 1
+    assert B * H > 1024
+    check(lengths, H, "f16", 900 + H, max_seqlen=70)
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_last_tile_takes_a_tail_of_up_to_16_keys_along(dtype):
     """Large launches (not the key-split form) run a last tile of 65..80 keys in one pass when at least two full
