@@ -415,7 +415,7 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
 #pragma unroll
         for (int j = 0; j < kRounds; ++j) asm volatile("" : : "v"((uint32_t)raw[j]));
         // (the loops over the rounds leave at the first round beyond n_tok: one scalar branch instead of a
-        // skipped block per round -- a taken branch costs as much as a dozen instructions here)
+        // skipped block per round -- a taken branch costs a lone wavefront as much as half a dozen instructions)
         uint64_t bits[kRounds];
 #pragma unroll
         for (int j = 0; j < kRounds; ++j) {

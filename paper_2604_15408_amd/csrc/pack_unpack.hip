@@ -54,7 +54,7 @@ void pack_kernel(const uint4* __restrict__ x, const uint8_t* __restrict__ keep, 
     // Rows of the chunk are dealt to the four wavefronts round-robin: set bit k -> wavefront k%4.
     // EARLY (chunk <= 16 and rows of at most 128 16-byte words): a wavefront has at most four rows
     // of two words per lane and requests them now, into registers.
-    // (the walks over the set bits are straight-line scalar code: a taken branch costs as much as a dozen
+    // (the walks over the set bits are straight-line scalar code: a taken branch costs a lone wavefront as much as half a dozen
     // instructions, so no loop per dropped bit)
     uint4 held[kMaxEarly][2];
     if (EARLY) {
