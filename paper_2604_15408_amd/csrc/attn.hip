@@ -311,8 +311,8 @@ __device__ __forceinline__ void tile_any(int rem, bool ext_tile, uint32_t tile0,
 // MODE kPadded: q, k, v, o are padded [B, N, H, D]; the group first turns image i's keep mask
 //   into the list of kept token positions (ballot + prefix over the group, in LDS) and then reads
 //   and writes rows through that list, so pack and unpack need no launch of their own.  With
-//   fill_mode 1 the q-tile-0 group of every (image, head) also zeroes that head's slice of the
-//   dropped rows of o.
+//   fill_mode 1 the groups of every (image, head) also zero that head's slice of the dropped rows
+//   of o, a share each.
 // MODE kStep  : the whole pack -> attention -> unpack step in this one launch.  q, k, v, o are
 //   packed as in kPacked, but the image's first row s is recounted from the keep mask (nonzero
 //   bytes before the image) and the kept-position list is built as in kPadded.  Besides its
@@ -403,7 +403,11 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         for (int j = 0; j < kRounds; ++j) raw[j] = load_byte_clamped(mask, j * kThreads + tid, n_tok);
         // Count first (one barrier): a group learns the image's length n before anything else is built, and
         // the groups of the upper-bound grid that have no rows leave here.
-        const bool zero_fill = fill_mode == 1 && m_tile == 0;  // this group zeroes the head's slice of the dropped rows
+        // fill_mode 1: the groups of an (image, head) share the zeroing of the head's slice of the dropped rows --
+        // group m takes every q_tiles-th pass of the group over the tokens, the groups without rows of their own
+        // (most of them, when much is pruned) included, before they leave
+        const bool zero_fill = fill_mode == 1;
+        const int fill_groups = (int)gridDim.y;
         // kStep, q-tile 0 (with short sequences: the groups that have rows): the count of the kept tokens in front of
         // the image shares the barrier of the length count, so the group knows s and n together.  The other q-tiles
         // count it after the test that lets most of them leave.
@@ -442,13 +446,13 @@ void attn_kernel(const void* __restrict__ index, int n_tok, int fill_mode, int H
         }
         if (zero_fill) {                                       // token t's keep bit: entry t / 64, bit t % 64
             if (MODE == kStep) {
-                for (int t = tid / 8; t < n_tok; t += kThreads / 8)
+                for (int t = tid / 8 + m_tile * (kThreads / 8); t < n_tok; t += fill_groups * (kThreads / 8))
                     if (((keep_bits[t >> 6] >> (t & 63)) & 1ull) == 0)
                         reinterpret_cast<uint4*>(step.out + (int64_t)(s + t) * tok_o + head_off)[tid % 8] =
                             make_uint4(0, 0, 0, 0);
             } else {
                 constexpr int kChunks = kHeadDim * (int)sizeof(OutT) / 16;
-                for (int t = tid / kChunks; t < n_tok; t += kThreads / kChunks)
+                for (int t = tid / kChunks + m_tile * (kThreads / kChunks); t < n_tok; t += fill_groups * (kThreads / kChunks))
                     if (((keep_bits[t >> 6] >> (t & 63)) & 1ull) == 0)
                         reinterpret_cast<uint4*>(o + (s + t) * tok_o + head_off)[tid % kChunks] = make_uint4(0, 0, 0, 0);
             }
