@@ -260,7 +260,7 @@ __global__ void noop_kernel() {}
 hipError_t launch_pack(const void* x, const uint8_t* keep, int B, int N, int C, void* packed,
                        int64_t cap_rows, int32_t* cu_seqlens, int32_t* gather_idx,
                        hipStream_t stream) {
-    const int chunk = pick_chunk(B, N);
+    const int chunk = pick_chunk(B, N, kPackMaxGroups);
     const int cpi = (N + chunk - 1) / chunk;
     // the early-load variant keeps the first 16 KB of mask prefix in registers; beyond that the
     // remaining prefix loads would queue behind the row loads, so larger masks take the plain order
@@ -283,7 +283,7 @@ hipError_t launch_unpack(const void* src, const uint8_t* keep, const int32_t* cu
                            static_cast<const uint4*>(src), cu_seqlens, gather_idx, B, C / 8,
                            static_cast<uint4*>(out));
     } else {
-        const int chunk = pick_chunk(B, N);
+        const int chunk = pick_chunk(B, N, kUnpackFillMaxGroups);
         const int cpi = (N + chunk - 1) / chunk;
         err = launch_kernel(unpack_fill_kernel, dim3(B * cpi), dim3(kBlockThreads), stream,
                            static_cast<const uint4*>(src), keep, cu_seqlens, N, C / 8,
