@@ -36,6 +36,8 @@ def check_pack(x_cpu, keep_cpu, cap=None):
     (1, 1, 8, 1.0, "f16"), (1, 7, 64, 0.5, "f16"), (2, 64, 64, 0.5, "bf16"), (3, 65, 192, 0.3, "f16"),
     (5, 197, 192, 0.2, "f16"), (4, 577, 768, 0.3, "f16"), (7, 130, 24, 1.0, "bf16"), (6, 33, 768, 0.0, "f16"),
     (32, 197, 768, 0.2, "f16"), (64, 197, 768, 0.7, "f16"), (3, 1000, 64, 0.05, "f16"),
+    # masks beyond 16 KB (the prefix count runs its remainder passes) and chunks of 16, 32 and 64 tokens
+    (100, 197, 64, 0.3, "f16"), (400, 197, 8, 0.5, "bf16"), (700, 197, 8, 0.2, "f16"),
 ])
 def test_pack_bit_exact(B, N, C, p, dtype):
     keep = wl.keep_bernoulli(B, N, p, 11 * B + N)
@@ -104,6 +106,7 @@ def test_pack_capacity_clamps_writes():
 @pytest.mark.parametrize("B,N,C,p,dtype", [
     (1, 1, 8, 1.0, "f16"), (2, 64, 64, 0.5, "bf16"), (3, 65, 192, 0.3, "f16"), (4, 577, 768, 0.3, "f16"),
     (32, 197, 768, 0.2, "f16"), (64, 197, 768, 0.7, "f16"), (5, 100, 64, 0.0, "f16"), (7, 130, 24, 1.0, "bf16"),
+    (200, 197, 64, 0.3, "f16"), (700, 197, 8, 0.2, "f16"),      # chunks of 16 and 64 tokens in the zero-filling form
 ])
 def test_unpack_bit_exact(B, N, C, p, dtype, fill_mode):
     keep = wl.keep_bernoulli(B, N, p, 13 * B + N)
