@@ -97,6 +97,14 @@ def test_serving_384_and_empty_images():
     check(wl.Workload("nothing", 3, 50, 2, 64, "f16", 32, torch.zeros(3, 50, dtype=torch.uint8)), 1)
 
 
+def test_masks_beyond_16_kb():
+    """From B*N > 16384 mask bytes on, the count of the kept tokens in front of an image runs its remainder
+    passes (q-tile 0 under the first barrier, the other q-tiles after it): 100 images of 197 tokens, lengths
+    around 59 (one q-tile) and around 118 (two)."""
+    check(wl.Workload("b100", 100, 197, 2, 64, "f16", 35, wl.keep_bernoulli(100, 197, 0.3, 12)), 1)
+    check(wl.Workload("b100w", 100, 197, 1, 64, "f16", 36, wl.keep_bernoulli(100, 197, 0.6, 13)), 0)
+
+
 def test_small_heads_and_odd_sizes():
     keep = wl.keep_bernoulli(7, 65, 0.5, 9)
     check(wl.Workload("odd", 7, 65, 1, 64, "f16", 33, keep), 0)
