@@ -63,6 +63,11 @@ def test_head_counts_and_several_dispatch_batches(H):
     check(lengths, H, "f16", 900 + H, max_seqlen=70)
 
 
+def test_loose_bound_many_surplus_q_tiles():
+    """A bound far above every length: 300 q-tiles in the second grid dimension, all but two of them without rows."""
+    check([40, 3, 70, 0, 129], 2, "f16", 4343, max_seqlen=64 * 300)
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_last_tile_takes_a_tail_of_up_to_16_keys_along(dtype):
     """Large launches (not the key-split form) run a last tile of 65..80 keys in one pass when at least two full
